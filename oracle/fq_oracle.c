@@ -1,0 +1,284 @@
+/*
+ * fq_oracle.c -- TEST INFRASTRUCTURE, not product code.
+ *
+ * Plain, slow, single-source CPU statement of what Fallback Quantization
+ * computes on the linear-layer GEMM path.  It exists so that the HIP library
+ * can be checked against something written straight from the paper.  Nothing
+ * in the product path may call it; only the test-suite, the smoke check and
+ * the benchmark's CPU-baseline leg load this file's shared object.  It shares
+ * no source, header, table or helper with the HIP library.
+ *
+ * What follows which passage of the paper (arXiv 2503.08040):
+ *   - block quantization  a = max|G| / 127,  Q^(G) = round(G / a),
+ *     dequantization Q(G) = a * Q^(G)                     : Sec. 3.1
+ *   - round = round-to-nearest (ties to even)             : Sec. 3.1
+ *   - two-step fallback quantization: quantize G, then quantize the residual
+ *     dQ(G) = G - Q(G) with a scale of its own            : Sec. 4.3
+ *   - fallback indicator u(i,k) = [max|G_ik| > theta]      : Sec. 4.4
+ *   - block GEMM, INT8 x INT8 -> INT32, dequantized by a^A * a^B and
+ *     accumulated in FP32                                  : Sec. 4.2, Eq. (1)
+ *   - fallback GEMM: k ascending; main term, then, if u(i,k)=1, the residual
+ *     term against the same B block                        : Sec. 4.3, Alg. 1
+ *   - the three linear-layer products  Y = X W^T,  dX = dY W,  dW = dY^T X
+ *                                                          : Sec. 3.2
+ *
+ * Arithmetic: the paper fixes INT8 codes, INT32 block products and an FP32
+ * accumulator.  It does not fix the precision in which a code is decided, so
+ * the decision is taken in IEEE binary32 (the precision the GPU kernel
+ * decides in), one operation at a time, round-to-nearest-even, no contraction
+ * (build with -ffp-contract=off), no flush-to-zero:
+ *     a  = amax / 127.0f            one division
+ *     q  = clamp(rintf(x / a))      one division, one rounding, clamp +-127
+ *     r  = fmaf(-(float)q, a, x)    residual, single rounding
+ *     a~ = max|r| / 127.0f ;  q~ = clamp(rintf(r / a~))
+ *     s  = a^A * a^B                one multiplication
+ *     acc = fmaf((float)P, s, acc)  P the exact INT32 block product
+ * An all-zero block has a = 0 and all codes 0 (no division is performed).
+ * Behaviour on NaN/Inf inputs is not defined by the paper: parity unpinned
+ * for non-finite inputs, and they are excluded from every test.
+ *
+ * Layouts (all host memory, all row-major, caller-allocated):
+ *   x_bf16     [rows, ld]            bf16 bit patterns (uint16)
+ *   codes      [rows, cols] int8     Q^(G)
+ *   scales     [nbr, nbc]   float    a_{i,k},  nbr = ceil(rows/g), nbc = ceil(cols/g)
+ *   mask       [nbr, nbc]   uint8    u(i,k)
+ *   res_codes  [rows, cols] int8     Q^(dQ(G)); zero outside flagged blocks
+ *   res_scales [nbr, nbc]   float    a~_{i,k}; zero outside flagged blocks
+ *   fb_list    [nbr*nbc]    int32    ascending ids (bi*nbc+bk) of flagged blocks
+ *   fb_count   [1]          int32
+ * Ragged edges: an edge block is the elements that exist.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+
+#define FQO_CRIT_NONE 0      /* u == 0 everywhere: plain block INT8, Eq. (1) */
+#define FQO_CRIT_ABSMAX_GT 1 /* u = [max|G| > theta], Sec. 4.4            */
+#define FQO_CRIT_ALL 2       /* u == 1 everywhere                           */
+
+#define FQO_OP_NT 0 /* C[M,N] = A[M,K] * B[N,K]^T   (Y  = X  W^T) */
+#define FQO_OP_NN 1 /* C[M,K] = A[M,N] * B[N,K]     (dX = dY W)   */
+#define FQO_OP_TN 2 /* C[N,K] = A[M,N]^T * B[M,K]   (dW = dY^T X) */
+
+static float bf16_to_f32(uint16_t h) {
+  uint32_t w = (uint32_t)h << 16;
+  float f;
+  memcpy(&f, &w, sizeof f);
+  return f;
+}
+
+/* fp32 -> bf16, round to nearest even (finite inputs). */
+static uint16_t f32_to_bf16_rne(float f) {
+  uint32_t w;
+  memcpy(&w, &f, sizeof w);
+  uint32_t lsb = (w >> 16) & 1u;
+  w += 0x7FFFu + lsb;
+  return (uint16_t)(w >> 16);
+}
+
+static int8_t quantize_one(float x, float a) {
+  float t = rintf(x / a); /* current rounding mode is the default: ties to even */
+  if (t > 127.0f) t = 127.0f;
+  if (t < -127.0f) t = -127.0f;
+  return (int8_t)t;
+}
+
+/* Sec. 3.1 (block quantization), Sec. 4.3 (residual step), Sec. 4.4 (u). */
+int fqo_quantize(const uint16_t *x_bf16, int rows, int cols, long ld, int g,
+                 int crit, float theta, int8_t *codes, float *scales,
+                 uint8_t *mask, int8_t *res_codes, float *res_scales,
+                 int32_t *fb_list, int32_t *fb_count) {
+  if (!x_bf16 || !codes || !scales || !mask || !res_codes || !res_scales ||
+      !fb_list || !fb_count)
+    return -1;
+  if (rows < 0 || cols < 0 || g < 1 || ld < cols) return -2;
+  if (crit < 0 || crit > 2) return -4;
+  int nbr = (rows + g - 1) / g, nbc = (cols + g - 1) / g;
+  int n_fb = 0;
+  for (int bi = 0; bi < nbr; ++bi) {
+    for (int bk = 0; bk < nbc; ++bk) {
+      int r0 = bi * g, r1 = r0 + g < rows ? r0 + g : rows;
+      int c0 = bk * g, c1 = c0 + g < cols ? c0 + g : cols;
+      /* step 1: a = max|G| / L */
+      float amax = 0.0f;
+      for (int r = r0; r < r1; ++r)
+        for (int c = c0; c < c1; ++c) {
+          float v = fabsf(bf16_to_f32(x_bf16[(size_t)r * ld + c]));
+          if (v > amax) amax = v;
+        }
+      float a = amax / 127.0f;
+      for (int r = r0; r < r1; ++r)
+        for (int c = c0; c < c1; ++c) {
+          float x = bf16_to_f32(x_bf16[(size_t)r * ld + c]);
+          codes[(size_t)r * cols + c] = (a == 0.0f) ? 0 : quantize_one(x, a);
+        }
+      scales[bi * nbc + bk] = a;
+      /* fallback decision */
+      int u;
+      if (crit == FQO_CRIT_NONE) u = 0;
+      else if (crit == FQO_CRIT_ALL) u = 1;
+      else u = (amax > theta) ? 1 : 0;
+      mask[bi * nbc + bk] = (uint8_t)u;
+      /* step 2 (flagged blocks only): quantize the residual G - Q(G) */
+      float ra = 0.0f;
+      if (u) {
+        float rmax = 0.0f;
+        for (int r = r0; r < r1; ++r)
+          for (int c = c0; c < c1; ++c) {
+            float x = bf16_to_f32(x_bf16[(size_t)r * ld + c]);
+            float res = fmaf(-(float)codes[(size_t)r * cols + c], a, x);
+            float v = fabsf(res);
+            if (v > rmax) rmax = v;
+          }
+        ra = rmax / 127.0f;
+        for (int r = r0; r < r1; ++r)
+          for (int c = c0; c < c1; ++c) {
+            float x = bf16_to_f32(x_bf16[(size_t)r * ld + c]);
+            float res = fmaf(-(float)codes[(size_t)r * cols + c], a, x);
+            res_codes[(size_t)r * cols + c] =
+                (ra == 0.0f) ? 0 : quantize_one(res, ra);
+          }
+        fb_list[n_fb++] = bi * nbc + bk;
+      } else {
+        for (int r = r0; r < r1; ++r)
+          for (int c = c0; c < c1; ++c) res_codes[(size_t)r * cols + c] = 0;
+      }
+      res_scales[bi * nbc + bk] = ra;
+    }
+  }
+  *fb_count = n_fb;
+  return 0;
+}
+
+/*
+ * A quantized operand as the GEMM sees it.  `codes`/`res_codes` are the
+ * [rows, cols] arrays written by fqo_quantize; rows/cols are those of the
+ * stored matrix (before any transposition the op implies).
+ */
+typedef struct {
+  int rows, cols;
+  const int8_t *codes;
+  const float *scales;
+  const uint8_t *mask;      /* may be NULL for the B operand */
+  const int8_t *res_codes;  /* may be NULL when mask is NULL */
+  const float *res_scales;
+} fqo_operand;
+
+/* Output shape and contraction length of each product. */
+static int op_dims(int op, const fqo_operand *A, const fqo_operand *B, int *Mo,
+                   int *No, int *Kc) {
+  switch (op) {
+  case FQO_OP_NT:
+    if (A->cols != B->cols) return -2;
+    *Mo = A->rows; *No = B->rows; *Kc = A->cols; return 0;
+  case FQO_OP_NN:
+    if (A->cols != B->rows) return -2;
+    *Mo = A->rows; *No = B->cols; *Kc = A->cols; return 0;
+  case FQO_OP_TN:
+    if (A->rows != B->rows) return -2;
+    *Mo = A->cols; *No = B->cols; *Kc = A->rows; return 0;
+  default:
+    return -4;
+  }
+}
+
+/* Element (i, t) of the left factor and (t, j) of the right factor, where i, j
+ * index the output and t the contraction; and the block-grid index of the
+ * quantization block that element lies in. */
+static size_t a_elem(int op, const fqo_operand *A, int i, int t) {
+  return op == FQO_OP_TN ? (size_t)t * A->cols + i : (size_t)i * A->cols + t;
+}
+static int a_block(int op, const fqo_operand *A, int g, int i, int t) {
+  int nbc = (A->cols + g - 1) / g;
+  return op == FQO_OP_TN ? (t / g) * nbc + i / g : (i / g) * nbc + t / g;
+}
+static size_t b_elem(int op, const fqo_operand *B, int t, int j) {
+  return op == FQO_OP_NT ? (size_t)j * B->cols + t : (size_t)t * B->cols + j;
+}
+static int b_block(int op, const fqo_operand *B, int g, int t, int j) {
+  int nbc = (B->cols + g - 1) / g;
+  return op == FQO_OP_NT ? (j / g) * nbc + t / g : (t / g) * nbc + j / g;
+}
+
+/*
+ * Alg. 1 for output rows [i0,i1) and columns [j0,j1).  Output elements are
+ * independent, so the tile loops of Alg. 1 are written per element; the
+ * k-block loop, the order of the two "+=" inside it and the FP32 accumulator
+ * are the algorithm's.  c_f32 (and c_bf16 if not NULL) are full [Mo, No]
+ * arrays; only the requested window is written.
+ */
+int fqo_gemm(int op, const fqo_operand *A, const fqo_operand *B, int g,
+             int i0, int i1, int j0, int j1, float *c_f32, uint16_t *c_bf16) {
+  if (!A || !B || !c_f32 || !A->codes || !A->scales || !B->codes || !B->scales)
+    return -1;
+  if (A->mask && (!A->res_codes || !A->res_scales)) return -1;
+  if (g < 1) return -3;
+  int Mo, No, Kc, rc = op_dims(op, A, B, &Mo, &No, &Kc);
+  if (rc) return rc;
+  if (i0 < 0 || i1 > Mo || j0 < 0 || j1 > No) return -2;
+  int nkb = (Kc + g - 1) / g;
+#pragma omp parallel for schedule(dynamic, 8)
+  for (int i = i0; i < i1; ++i) {
+    for (int j = j0; j < j1; ++j) {
+      float acc = 0.0f;
+      for (int kb = 0; kb < nkb; ++kb) {
+        int t0 = kb * g, t1 = t0 + g < Kc ? t0 + g : Kc;
+        int ab = a_block(op, A, g, i, t0), bb = b_block(op, B, g, t0, j);
+        int32_t P = 0;
+        for (int t = t0; t < t1; ++t)
+          P += (int32_t)A->codes[a_elem(op, A, i, t)] *
+               (int32_t)B->codes[b_elem(op, B, t, j)];
+        float s = A->scales[ab] * B->scales[bb];
+        acc = fmaf((float)P, s, acc);
+        if (A->mask && A->mask[ab]) {
+          int32_t Pr = 0;
+          for (int t = t0; t < t1; ++t)
+            Pr += (int32_t)A->res_codes[a_elem(op, A, i, t)] *
+                  (int32_t)B->codes[b_elem(op, B, t, j)];
+          float sr = A->res_scales[ab] * B->scales[bb];
+          acc = fmaf((float)Pr, sr, acc);
+        }
+      }
+      c_f32[(size_t)i * No + j] = acc;
+      if (c_bf16) c_bf16[(size_t)i * No + j] = f32_to_bf16_rne(acc);
+    }
+  }
+  return 0;
+}
+
+/* The INT32 block product of one k-block (main or residual term) for the
+ * window [i0,i1) x [j0,j1); p_out is a full [Mo, No] array.  The residual
+ * product of an unflagged block is 0. */
+int fqo_gemm_partials(int op, const fqo_operand *A, const fqo_operand *B, int g,
+                      int kb, int residual_term, int i0, int i1, int j0,
+                      int j1, int32_t *p_out) {
+  if (!A || !B || !p_out || !A->codes || !B->codes) return -1;
+  if (residual_term && (!A->mask || !A->res_codes)) return -1;
+  if (g < 1) return -3;
+  int Mo, No, Kc, rc = op_dims(op, A, B, &Mo, &No, &Kc);
+  if (rc) return rc;
+  int nkb = (Kc + g - 1) / g;
+  if (kb < 0 || kb >= nkb) return -2;
+  if (i0 < 0 || i1 > Mo || j0 < 0 || j1 > No) return -2;
+  int t0 = kb * g, t1 = t0 + g < Kc ? t0 + g : Kc;
+  const int8_t *ac = residual_term ? A->res_codes : A->codes;
+  for (int i = i0; i < i1; ++i)
+    for (int j = j0; j < j1; ++j) {
+      int32_t P = 0;
+      if (!residual_term || A->mask[a_block(op, A, g, i, t0)])
+        for (int t = t0; t < t1; ++t)
+          P += (int32_t)ac[a_elem(op, A, i, t)] *
+               (int32_t)B->codes[b_elem(op, B, t, j)];
+      p_out[(size_t)i * No + j] = P;
+    }
+  return 0;
+}
+
+/* Number of OpenMP threads fqo_gemm will use (1 when built without OpenMP). */
+#ifdef _OPENMP
+#include <omp.h>
+int fqo_num_threads(void) { return omp_get_max_threads(); }
+#else
+int fqo_num_threads(void) { return 1; }
+#endif

@@ -1,0 +1,130 @@
+"""ctypes loader for the CPU oracle (TEST INFRASTRUCTURE, not product code).
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this.
+The functions here marshal numpy arrays into oracle/fq_oracle.c and hold none
+of the method's arithmetic.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+CRIT_NONE, CRIT_ABSMAX_GT, CRIT_ALL = 0, 1, 2
+OP_NT, OP_NN, OP_TN = 0, 1, 2
+
+
+class _Operand(C.Structure):
+    _fields_ = [("rows", C.c_int), ("cols", C.c_int),
+                ("codes", C.c_void_p), ("scales", C.c_void_p), ("mask", C.c_void_p),
+                ("res_codes", C.c_void_p), ("res_scales", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        _lib = C.CDLL(path)
+        _lib.fqo_quantize.restype = C.c_int
+        _lib.fqo_quantize.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_long, C.c_int, C.c_int,
+                                      C.c_float] + [C.c_void_p] * 7
+        _lib.fqo_gemm.restype = C.c_int
+        _lib.fqo_gemm.argtypes = [C.c_int, C.POINTER(_Operand), C.POINTER(_Operand), C.c_int,
+                                  C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        _lib.fqo_gemm_partials.restype = C.c_int
+        _lib.fqo_gemm_partials.argtypes = [C.c_int, C.POINTER(_Operand), C.POINTER(_Operand),
+                                           C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
+                                           C.c_int, C.c_void_p]
+        _lib.fqo_num_threads.restype = C.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().fqo_num_threads())
+
+
+class QTensor:
+    """Outputs of the oracle quantizer for one matrix (all numpy, row-major)."""
+
+    def __init__(self, rows, cols, g):
+        self.rows, self.cols, self.g = rows, cols, g
+        self.nbr, self.nbc = -(-rows // g), -(-cols // g)
+        self.codes = np.zeros((rows, cols), np.int8)
+        self.scales = np.zeros((self.nbr, self.nbc), np.float32)
+        self.mask = np.zeros((self.nbr, self.nbc), np.uint8)
+        self.res_codes = np.zeros((rows, cols), np.int8)
+        self.res_scales = np.zeros((self.nbr, self.nbc), np.float32)
+        self.fb_list = np.full((max(1, self.nbr * self.nbc),), -1, np.int32)
+        self.fb_count = np.zeros((1,), np.int32)
+
+    def operand(self, with_fallback=True):
+        o = _Operand()
+        o.rows, o.cols = self.rows, self.cols
+        o.codes = self.codes.ctypes.data
+        o.scales = self.scales.ctypes.data
+        if with_fallback:
+            o.mask = self.mask.ctypes.data
+            o.res_codes = self.res_codes.ctypes.data
+            o.res_scales = self.res_scales.ctypes.data
+        else:
+            o.mask = o.res_codes = o.res_scales = None
+        return o
+
+
+def quantize(x_bf16: np.ndarray, g: int, crit: int, theta: float) -> QTensor:
+    """x_bf16: 2-D uint16 array of bf16 bit patterns (row stride may exceed cols)."""
+    assert x_bf16.dtype == np.uint16 and x_bf16.ndim == 2
+    assert x_bf16.strides[1] == 2 and x_bf16.strides[0] % 2 == 0
+    rows, cols = x_bf16.shape
+    ld = x_bf16.strides[0] // 2 if rows > 1 else max(cols, 1)
+    q = QTensor(rows, cols, g)
+    rc = lib().fqo_quantize(x_bf16.ctypes.data, rows, cols, ld, g, crit, C.c_float(theta),
+                            q.codes.ctypes.data, q.scales.ctypes.data, q.mask.ctypes.data,
+                            q.res_codes.ctypes.data, q.res_scales.ctypes.data,
+                            q.fb_list.ctypes.data, q.fb_count.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"fqo_quantize failed: {rc}")
+    return q
+
+
+def out_shape(op, A: QTensor, B: QTensor):
+    if op == OP_NT:
+        return A.rows, B.rows
+    if op == OP_NN:
+        return A.rows, B.cols
+    if op == OP_TN:
+        return A.cols, B.cols
+    raise ValueError(op)
+
+
+def gemm(op, A: QTensor, B: QTensor, window=None, want_bf16=False, a_fallback=True):
+    """Alg. 1 on the window (i0, i1, j0, j1) of the output (default: all of it).
+
+    Returns the full-shape fp32 array (zeros outside the window) and, if asked,
+    the bf16 bit patterns."""
+    Mo, No = out_shape(op, A, B)
+    i0, i1, j0, j1 = window if window is not None else (0, Mo, 0, No)
+    c = np.zeros((Mo, No), np.float32)
+    cb = np.zeros((Mo, No), np.uint16) if want_bf16 else None
+    oa, ob = A.operand(a_fallback), B.operand(False)
+    rc = lib().fqo_gemm(op, C.byref(oa), C.byref(ob), A.g, i0, i1, j0, j1, c.ctypes.data,
+                        cb.ctypes.data if cb is not None else None)
+    if rc != 0:
+        raise RuntimeError(f"fqo_gemm failed: {rc}")
+    return (c, cb) if want_bf16 else c
+
+
+def gemm_partials(op, A: QTensor, B: QTensor, kb: int, residual_term: bool, window=None):
+    Mo, No = out_shape(op, A, B)
+    i0, i1, j0, j1 = window if window is not None else (0, Mo, 0, No)
+    p = np.zeros((Mo, No), np.int32)
+    oa, ob = A.operand(True), B.operand(False)
+    rc = lib().fqo_gemm_partials(op, C.byref(oa), C.byref(ob), A.g, kb, int(residual_term),
+                                 i0, i1, j0, j1, p.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"fqo_gemm_partials failed: {rc}")
+    return p
