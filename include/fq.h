@@ -1,0 +1,181 @@
+/*
+ * fq.h -- C ABI of libfq: Fallback Quantization for AMD MI355X (gfx950).
+ *
+ * The library implements the linear-layer hot path of "Accurate INT8 Training
+ * Through Dynamic Block-Level Fallback" (arXiv 2503.08040):
+ *
+ *   fq_quantize  block INT8 quantization of a bf16 matrix with per-block scale
+ *                (Sec. 3.1), run-time outlier detection u = [max|G| > theta]
+ *                (Sec. 4.4) and, for flagged blocks, the second quantization
+ *                step on the residual (Sec. 4.3);
+ *   fq_gemm      the fallback block GEMM (Sec. 4.2 Eq. (1), Sec. 4.3 Alg. 1) for
+ *                the three products of a linear layer (Sec. 3.2):
+ *                Y = X W^T, dX = dY W, dW = dY^T X.
+ *
+ * General rules
+ *   - Every data pointer is caller-owned DEVICE memory (hipMalloc'ed or a
+ *     PyTorch CUDA/HIP tensor's storage) unless a comment says "host".  The
+ *     library never allocates, frees or retains device memory and keeps no
+ *     state between calls.  fq_qtensor structs themselves live in host memory.
+ *   - Calls enqueue kernels on `hip_stream` (a hipStream_t passed as void*;
+ *     NULL is the default stream) and return without waiting.
+ *   - Arguments are validated on the host before anything is launched; a
+ *     failed validation returns a negative fq_status and launches nothing.
+ *     HIP launch failures are returned as FQ_ERR_HIP.  No exception crosses
+ *     this boundary.
+ *   - The quantization block is 128 x 128 (FQ_BLOCK); other sizes return
+ *     FQ_ERR_BLOCK.  Matrix dimensions need not be multiples of 128: an edge
+ *     block consists of the elements that exist, the rest counts as zero.
+ *
+ * Storage order of INT8 codes ("tile order")
+ *   Codes are not stored row-major.  A rows x cols matrix is cut into
+ *   nbr x nbc blocks (nbr = ceil(rows/128), nbc = ceil(cols/128)); block
+ *   (bi, bk) occupies the 16384 bytes starting at (bi*nbc + bk)*16384, and
+ *   element (r, c) of the block (0 <= r, c < 128) is the byte at
+ *       ((r/32)*4 + c/32)*1024 + ((r%32) + 32*((c%32)/16))*16 + c%16 .
+ *   This is the operand order of the gfx950 INT8 matrix instruction
+ *   (32x32x32): every 1 KiB run is one wavefront-wide operand fragment, 16
+ *   contraction-contiguous bytes per lane, so the GEMM streams blocks with
+ *   perfectly coalesced 16-byte accesses and no shuffling.  Padding elements
+ *   of edge blocks are stored as 0.  `codes_t` holds the transposed matrix
+ *   (cols x rows) in the same order; it is what the backward products read
+ *   when the contraction runs along the rows of the stored matrix.
+ *   fq_codes_to_rowmajor converts back to a plain row-major array.
+ */
+#ifndef FQ_H_
+#define FQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FQ_BLOCK 128
+#define FQ_BLOCK_BYTES 16384
+
+typedef enum {
+  FQ_OK = 0,
+  FQ_ERR_NULL = -1,     /* a required pointer is NULL                          */
+  FQ_ERR_SHAPE = -2,    /* negative / inconsistent dimensions or strides       */
+  FQ_ERR_BLOCK = -3,    /* block size other than 128                           */
+  FQ_ERR_ENUM = -4,     /* unknown enum value, or B operand quantized with fallback */
+  FQ_ERR_CAPACITY = -5, /* more flagged blocks than `capacity` (fq_qtensor_check) */
+  FQ_ERR_HIP = -6       /* a HIP call failed                                   */
+} fq_status;
+
+/* Fallback criterion.  NONE: u = 0 everywhere (plain block INT8, Eq. (1)).
+ * ABSMAX_GT: u(i,k) = [max|G_ik| > theta], strict (Sec. 4.4).  ALL: u = 1. */
+typedef enum { FQ_CRIT_NONE = 0, FQ_CRIT_ABSMAX_GT = 1, FQ_CRIT_ALL = 2 } fq_criterion;
+
+/* Which product of the linear layer (Sec. 3.2).  A is the operand that may
+ * carry fallback blocks (Alg. 1 defines fallback for A only).
+ *   NT: C[M,N] = A[M,K] * B[N,K]^T     Y  = X  W^T
+ *   NN: C[M,K] = A[M,N] * B[N,K]       dX = dY W      (needs B->codes_t)
+ *   TN: C[N,K] = A[M,N]^T * B[M,K]     dW = dY^T X    (needs A->codes_t,
+ *                                       A->res_codes_t if A has fallback, B->codes_t) */
+typedef enum { FQ_OP_NT = 0, FQ_OP_NN = 1, FQ_OP_TN = 2 } fq_op;
+
+typedef enum { FQ_OUT_F32 = 0, FQ_OUT_BF16 = 1 } fq_out_dtype;
+
+/*
+ * A quantized matrix.  The struct is host memory; every pointer in it is
+ * device memory owned by the caller.  fq_qtensor_bind fills the pointers from
+ * one allocation of fq_qtensor_bytes bytes; a caller may also set them itself.
+ */
+typedef struct {
+  int32_t rows, cols;    /* shape of the source matrix                           */
+  int32_t block;         /* 128                                                  */
+  int32_t capacity;      /* number of residual slots the res_* buffers hold      */
+  int32_t criterion;     /* host: fq_criterion of the last fq_quantize into this */
+  int32_t reserved;
+  int8_t *codes;         /* [nbr*nbc][16384] tile order, Q^(G)        (Sec. 3.1) */
+  int8_t *codes_t;       /* [nbc*nbr][16384] tile order of G^T, or NULL          */
+  float *scales;         /* [nbr, nbc]  a_{i,k} = max|G_ik| / 127     (Sec. 3.1) */
+  uint8_t *mask;         /* [nbr, nbc]  u(i,k)                        (Sec. 4.4) */
+  int32_t *fb_count;     /* [1]  number of flagged blocks (may exceed capacity)  */
+  int32_t *fb_list;      /* [nbr*nbc] ascending ids bi*nbc+bk of flagged blocks;
+                            entries past fb_count are -1                         */
+  int32_t *fb_slot;      /* [nbr, nbc] residual slot of the block, -1 if not
+                            flagged, -2 if flagged but no slot was left. Slots
+                            are a bijection onto [0, fb_count) in no fixed order */
+  int8_t *res_codes;     /* [capacity][16384] tile order, Q^(dQ(G))   (Sec. 4.3) */
+  int8_t *res_codes_t;   /* [capacity][16384] tile order of the transposed
+                            residual block, or NULL                              */
+  float *res_scales;     /* [capacity]  a~ of the block in that slot  (Sec. 4.3) */
+} fq_qtensor;
+
+/* Bytes of device memory fq_qtensor_bind needs for a rows x cols matrix with
+ * `capacity` residual slots (0 <= capacity <= nbr*nbc; nbr*nbc can never
+ * overflow).  Returns 0 on invalid arguments.  Host-only, no HIP call. */
+size_t fq_qtensor_bytes(int32_t rows, int32_t cols, int32_t block, int32_t capacity,
+                        int want_transposed);
+
+/* Carve the buffers of `out` from `base` (device, 256-byte aligned, at least
+ * fq_qtensor_bytes bytes) and fill the scalar fields.  Host-only. */
+fq_status fq_qtensor_bind(void *base, int32_t rows, int32_t cols, int32_t block,
+                          int32_t capacity, int want_transposed, fq_qtensor *out);
+
+/*
+ * Quantize x_bf16 (device, row-major [rows, ld] bf16, ld >= cols) into `out`.
+ *   per block: a = max|G|/127, codes = round-to-nearest-even(G/a) clamped to
+ *   +-127 (Sec. 3.1); u from `crit`/`theta` (Sec. 4.4); for u = 1 the residual
+ *   G - a*codes is quantized the same way into a residual slot (Sec. 4.3).
+ *   An all-zero block has scale 0 and codes 0.  Arithmetic is IEEE binary32,
+ *   division correctly rounded.  Non-finite inputs give unspecified codes.
+ * Outputs: every buffer of `out` that is not NULL-optional (codes, scales,
+ * mask, fb_count, fb_list, fb_slot; res_* when capacity > 0; *_t when set).
+ * out->capacity may be 0 only with FQ_CRIT_NONE.  If more blocks are flagged
+ * than there are slots, the surplus blocks get fb_slot = -2, fb_count still
+ * reports the true count, and any fq_gemm using the tensor as A writes NaN to
+ * the affected output rows; fq_qtensor_check reports FQ_ERR_CAPACITY.
+ * Errors: FQ_ERR_NULL, FQ_ERR_SHAPE (rows/cols < 0, ld < cols), FQ_ERR_BLOCK,
+ * FQ_ERR_ENUM, FQ_ERR_CAPACITY (capacity 0 with a fallback criterion),
+ * FQ_ERR_HIP.  rows == 0 or cols == 0 is valid and only zeroes fb_count.
+ */
+fq_status fq_quantize(const void *x_bf16, int32_t rows, int32_t cols, int64_t ld,
+                      int32_t block, fq_criterion crit, float theta, fq_qtensor *out,
+                      void *hip_stream);
+
+/*
+ * Fallback block GEMM (Alg. 1).  For every output tile, k-blocks ascending:
+ *   C += float(P) * (a^A_ik * a^B_kj),  P the exact INT32 product of the code blocks,
+ *   and, if u(i,k) = 1,  C += float(P~) * (a~^A_ik * a^B_kj)  with the residual
+ *   codes of A against the same B block.  C is accumulated in FP32 by fused
+ *   multiply-adds in exactly this order and stored as fp32 or as bf16
+ *   (round-to-nearest-even).
+ * C: device, row-major [Mout, ldc] of `cdt`, ldc >= Nout (see fq_op for shapes).
+ * B must have been quantized with FQ_CRIT_NONE.
+ * Errors: FQ_ERR_NULL (also a missing *_t buffer the op needs), FQ_ERR_SHAPE
+ * (contraction lengths differ, ldc < Nout), FQ_ERR_BLOCK, FQ_ERR_ENUM, FQ_ERR_HIP.
+ * An empty output (Mout or Nout 0) is valid and launches nothing; an empty
+ * contraction writes zeros.
+ */
+fq_status fq_gemm(fq_op op, const fq_qtensor *A, const fq_qtensor *B, void *C,
+                  fq_out_dtype cdt, int64_t ldc, void *hip_stream);
+
+/* The INT32 block product of k-block `k_block` alone (Alg. 1's INT x INT
+ * product before dequantization): main term (residual_term = 0) or residual
+ * term (1; zero for unflagged blocks).  p_out: device int32 [Mout, Nout]
+ * row-major, dense.  Same validation as fq_gemm plus 0 <= k_block < nkb. */
+fq_status fq_gemm_debug_partials(fq_op op, const fq_qtensor *A, const fq_qtensor *B,
+                                 int32_t k_block, int residual_term, int32_t *p_out,
+                                 void *hip_stream);
+
+/* Convert tile-order codes (nbr*nbc blocks of a rows x cols matrix) to a dense
+ * row-major int8 [rows, cols] array (device).  For inspection and tests. */
+fq_status fq_codes_to_rowmajor(const int8_t *tiled, int32_t rows, int32_t cols,
+                               int8_t *dense, void *hip_stream);
+
+/* Waits for `hip_stream`, reads fb_count back and returns FQ_ERR_CAPACITY if it
+ * exceeds t->capacity, FQ_OK otherwise; *count_out (host, may be NULL) gets the count. */
+fq_status fq_qtensor_check(const fq_qtensor *t, int32_t *count_out, void *hip_stream);
+
+/* Static, never-NULL description of a status code (host). */
+const char *fq_status_string(fq_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FQ_H_ */

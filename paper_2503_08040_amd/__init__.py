@@ -1,0 +1,211 @@
+"""Python binding of libfq (Fallback Quantization on MI355X).
+
+Thin ctypes layer over the C ABI declared in include/fq.h: same names, argument
+marshalling only.  PyTorch supplies device memory and the current stream; every
+step of the path runs in the library's HIP kernels.  If the compiled library is
+missing, importing this package's functions raises -- there is no fallback.
+"""
+import ctypes as C
+import os
+
+FQ_BLOCK = 128
+FQ_BLOCK_BYTES = 16384
+
+FQ_OK, FQ_ERR_NULL, FQ_ERR_SHAPE, FQ_ERR_BLOCK, FQ_ERR_ENUM, FQ_ERR_CAPACITY, FQ_ERR_HIP = \
+    0, -1, -2, -3, -4, -5, -6
+FQ_CRIT_NONE, FQ_CRIT_ABSMAX_GT, FQ_CRIT_ALL = 0, 1, 2
+FQ_OP_NT, FQ_OP_NN, FQ_OP_TN = 0, 1, 2
+FQ_OUT_F32, FQ_OUT_BF16 = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfq.so")
+
+EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_gemm",
+           "fq_gemm_debug_partials", "fq_codes_to_rowmajor", "fq_qtensor_check",
+           "fq_status_string"]
+
+
+class fq_qtensor(C.Structure):
+    """Mirror of the C struct fq_qtensor."""
+    _fields_ = [("rows", C.c_int32), ("cols", C.c_int32), ("block", C.c_int32),
+                ("capacity", C.c_int32), ("criterion", C.c_int32), ("reserved", C.c_int32),
+                ("codes", C.c_void_p), ("codes_t", C.c_void_p), ("scales", C.c_void_p),
+                ("mask", C.c_void_p), ("fb_count", C.c_void_p), ("fb_list", C.c_void_p),
+                ("fb_slot", C.c_void_p), ("res_codes", C.c_void_p), ("res_codes_t", C.c_void_p),
+                ("res_scales", C.c_void_p)]
+
+
+class FqError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                               "`python -m paper_2503_08040_amd.build` (needs hipcc)")
+        L = C.CDLL(LIB_PATH)
+        L.fq_qtensor_bytes.restype = C.c_size_t
+        L.fq_qtensor_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int]
+        L.fq_qtensor_bind.restype = C.c_int
+        L.fq_qtensor_bind.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                      C.c_int, C.POINTER(fq_qtensor)]
+        L.fq_quantize.restype = C.c_int
+        L.fq_quantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int,
+                                  C.c_float, C.POINTER(fq_qtensor), C.c_void_p]
+        L.fq_gemm.restype = C.c_int
+        L.fq_gemm.argtypes = [C.c_int, C.POINTER(fq_qtensor), C.POINTER(fq_qtensor), C.c_void_p,
+                              C.c_int, C.c_int64, C.c_void_p]
+        L.fq_gemm_debug_partials.restype = C.c_int
+        L.fq_gemm_debug_partials.argtypes = [C.c_int, C.POINTER(fq_qtensor), C.POINTER(fq_qtensor),
+                                             C.c_int32, C.c_int, C.c_void_p, C.c_void_p]
+        L.fq_codes_to_rowmajor.restype = C.c_int
+        L.fq_codes_to_rowmajor.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.fq_qtensor_check.restype = C.c_int
+        L.fq_qtensor_check.argtypes = [C.POINTER(fq_qtensor), C.POINTER(C.c_int32), C.c_void_p]
+        L.fq_status_string.restype = C.c_char_p
+        L.fq_status_string.argtypes = [C.c_int]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().fq_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != FQ_OK:
+        raise FqError(status, where)
+
+
+def _stream_ptr(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def fq_qtensor_bytes(rows, cols, capacity, want_transposed=False, block=FQ_BLOCK) -> int:
+    return int(lib().fq_qtensor_bytes(rows, cols, block, capacity, int(want_transposed)))
+
+
+class QTensor:
+    """Device buffers of one quantized matrix: a torch byte tensor carved up by
+    fq_qtensor_bind, plus typed views of its pieces for inspection."""
+
+    def __init__(self, rows, cols, capacity=None, want_transposed=False, device="cuda"):
+        import torch
+        self.rows, self.cols = int(rows), int(cols)
+        self.nbr, self.nbc = -(-self.rows // FQ_BLOCK), -(-self.cols // FQ_BLOCK)
+        self.capacity = self.nbr * self.nbc if capacity is None else int(capacity)
+        self.want_transposed = bool(want_transposed)
+        nbytes = fq_qtensor_bytes(self.rows, self.cols, self.capacity, self.want_transposed)
+        if nbytes == 0:
+            raise FqError(FQ_ERR_SHAPE, "fq_qtensor_bytes")
+        self.storage = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
+        self._base = (self.storage.data_ptr() + 255) & ~255
+        self.c = fq_qtensor()
+        _check(lib().fq_qtensor_bind(C.c_void_p(self._base), self.rows, self.cols, FQ_BLOCK,
+                                     self.capacity, int(self.want_transposed), C.byref(self.c)),
+               "fq_qtensor_bind")
+
+    def _view(self, ptr, nbytes, dtype, shape):
+        import torch
+        off = ptr - self.storage.data_ptr()
+        return self.storage[off:off + nbytes].view(dtype).view(shape)
+
+    def view(self, field):
+        """Typed torch view of one buffer (device memory, no copy)."""
+        import torch
+        nb = self.nbr * self.nbc
+        spec = {
+            "codes": (torch.int8, (nb, FQ_BLOCK_BYTES), 1),
+            "codes_t": (torch.int8, (nb, FQ_BLOCK_BYTES), 1),
+            "scales": (torch.float32, (self.nbr, self.nbc), 4),
+            "mask": (torch.uint8, (self.nbr, self.nbc), 1),
+            "fb_count": (torch.int32, (1,), 4),
+            "fb_list": (torch.int32, (nb,), 4),
+            "fb_slot": (torch.int32, (self.nbr, self.nbc), 4),
+            "res_codes": (torch.int8, (self.capacity, FQ_BLOCK_BYTES), 1),
+            "res_codes_t": (torch.int8, (self.capacity, FQ_BLOCK_BYTES), 1),
+            "res_scales": (torch.float32, (self.capacity,), 4),
+        }[field]
+        ptr = getattr(self.c, field)
+        if not ptr:
+            return None
+        n = 1
+        for d in spec[1]:
+            n *= d
+        return self._view(ptr, n * spec[2], spec[0], spec[1])
+
+
+def fq_quantize(x, crit, theta, out: QTensor = None, capacity=None, want_transposed=False,
+                stream=None) -> QTensor:
+    """x: 2-D torch.bfloat16 CUDA tensor with unit column stride."""
+    import torch
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.is_cuda
+    assert x.stride(1) == 1 or x.shape[1] <= 1
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else max(cols, 1)
+    if out is None:
+        out = QTensor(rows, cols, capacity, want_transposed, x.device)
+    _check(lib().fq_quantize(C.c_void_p(x.data_ptr()), rows, cols, ld, FQ_BLOCK, int(crit),
+                             C.c_float(theta), C.byref(out.c), _stream_ptr(stream)), "fq_quantize")
+    return out
+
+
+def gemm_out_shape(op, A: QTensor, B: QTensor):
+    if op == FQ_OP_NT:
+        return A.rows, B.rows
+    if op == FQ_OP_NN:
+        return A.rows, B.cols
+    if op == FQ_OP_TN:
+        return A.cols, B.cols
+    raise FqError(FQ_ERR_ENUM, "fq_gemm")
+
+
+def fq_gemm(op, A: QTensor, B: QTensor, out=None, out_dtype=None, stream=None):
+    """C = A (op) B per Alg. 1; out is a 2-D float32 or bfloat16 CUDA tensor."""
+    import torch
+    Mo, No = gemm_out_shape(op, A, B)
+    if out is None:
+        out = torch.empty((Mo, No), dtype=out_dtype or torch.float32, device=A.storage.device)
+    assert out.shape == (Mo, No) and (out.stride(1) == 1 or No <= 1)
+    cdt = {torch.float32: FQ_OUT_F32, torch.bfloat16: FQ_OUT_BF16}[out.dtype]
+    ldc = out.stride(0) if Mo > 1 else max(No, 1)
+    _check(lib().fq_gemm(int(op), C.byref(A.c), C.byref(B.c), C.c_void_p(out.data_ptr()), cdt,
+                         ldc, _stream_ptr(stream)), "fq_gemm")
+    return out
+
+
+def fq_gemm_debug_partials(op, A: QTensor, B: QTensor, k_block, residual_term, stream=None):
+    import torch
+    Mo, No = gemm_out_shape(op, A, B)
+    out = torch.zeros((Mo, No), dtype=torch.int32, device=A.storage.device)
+    _check(lib().fq_gemm_debug_partials(int(op), C.byref(A.c), C.byref(B.c), int(k_block),
+                                        int(bool(residual_term)), C.c_void_p(out.data_ptr()),
+                                        _stream_ptr(stream)), "fq_gemm_debug_partials")
+    return out
+
+
+def fq_codes_to_rowmajor(tiled, rows, cols, stream=None):
+    """tiled: int8 CUDA tensor in tile order (a QTensor 'codes' view)."""
+    import torch
+    dense = torch.empty((rows, cols), dtype=torch.int8, device=tiled.device)
+    _check(lib().fq_codes_to_rowmajor(C.c_void_p(tiled.data_ptr()), rows, cols,
+                                      C.c_void_p(dense.data_ptr()), _stream_ptr(stream)),
+           "fq_codes_to_rowmajor")
+    return dense
+
+
+def fq_qtensor_check(t: QTensor, stream=None) -> int:
+    """Synchronizes; returns the number of flagged blocks, raises on capacity overflow."""
+    n = C.c_int32(0)
+    _check(lib().fq_qtensor_check(C.byref(t.c), C.byref(n), _stream_ptr(stream)), "fq_qtensor_check")
+    return int(n.value)

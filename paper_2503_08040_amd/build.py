@@ -1,0 +1,43 @@
+"""Compile the HIP sources into paper_2503_08040_amd/libfq.so (gfx950 only)."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libfq.so")
+SOURCES = ["fq_api.hip", "fq_quantize.hip", "fq_gemm.hip"]
+HEADERS = ["fq_device.h", "fq_kernels.h", os.path.join("..", "..", "include", "fq.h")]
+
+# Packed FP32 VALU instructions are switched off for the device pass (the host
+# pass prints a harmless "not a recognized feature" note).
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-Wall", "-Wno-unused-command-line-argument"]
+
+
+def stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, f) for f in SOURCES + HEADERS]
+    return any(os.path.getmtime(d) > t for d in deps)
+
+
+def build(force: bool = True, extra_flags=()) -> str:
+    if not force and not stale():
+        return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-o", LIB] + \
+          [os.path.join(CSRC, f) for f in SOURCES]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    noise = "is not a recognized feature for this target"
+    err = "\n".join(ln for ln in r.stderr.splitlines() if noise not in ln)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed:\n{err}")
+    if err.strip():
+        print(err)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())

@@ -1,0 +1,232 @@
+// C ABI of libfq: argument validation and marshalling into kernel launches.
+// Everything is checked on the host before the first HIP call.
+#include "../../include/fq.h"
+
+#include <hip/hip_runtime.h>
+
+#include "fq_device.h"
+#include "fq_kernels.h"
+
+namespace {
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct Layout {
+  size_t codes, codes_t, scales, mask, fb_count, fb_list, fb_slot, res_codes, res_codes_t,
+      res_scales, total;
+};
+
+bool compute_layout(int32_t rows, int32_t cols, int32_t block, int32_t capacity, int want_t,
+                    Layout* L) {
+  if (rows < 0 || cols < 0 || block != FQ_BLOCK || capacity < 0) return false;
+  const int64_t nb = ceil_div(rows, FQ_BLOCK) * ceil_div(cols, FQ_BLOCK);
+  if (capacity > nb || nb > (int64_t)1 << 30) return false;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes ? bytes : 1); return o; };
+  L->codes = take((size_t)nb * FQ_BLOCK_BYTES);
+  L->codes_t = want_t ? take((size_t)nb * FQ_BLOCK_BYTES) : (size_t)-1;
+  L->scales = take((size_t)nb * 4);
+  L->mask = take((size_t)nb);
+  L->fb_count = take(4);
+  L->fb_list = take((size_t)nb * 4);
+  L->fb_slot = take((size_t)nb * 4);
+  L->res_codes = take((size_t)capacity * FQ_BLOCK_BYTES);
+  L->res_codes_t = want_t ? take((size_t)capacity * FQ_BLOCK_BYTES) : (size_t)-1;
+  L->res_scales = take((size_t)capacity * 4);
+  L->total = off;
+  return true;
+}
+
+fq_status check_qtensor(const fq_qtensor* t) {
+  if (!t) return FQ_ERR_NULL;
+  if (t->block != FQ_BLOCK) return FQ_ERR_BLOCK;
+  if (t->rows < 0 || t->cols < 0 || t->capacity < 0) return FQ_ERR_SHAPE;
+  if (!t->codes || !t->scales || !t->mask || !t->fb_count || !t->fb_list || !t->fb_slot)
+    return FQ_ERR_NULL;
+  if (t->capacity > 0 && (!t->res_codes || !t->res_scales)) return FQ_ERR_NULL;
+  if (t->capacity > 0 && t->codes_t && !t->res_codes_t) return FQ_ERR_NULL;
+  return FQ_OK;
+}
+
+// Validates a GEMM call and fills the kernel parameters (without the output).
+fq_status prepare_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, fq::GemmParams* g) {
+  fq_status s = check_qtensor(A);
+  if (s != FQ_OK) return s;
+  s = check_qtensor(B);
+  if (s != FQ_OK) return s;
+  if (op != FQ_OP_NT && op != FQ_OP_NN && op != FQ_OP_TN) return FQ_ERR_ENUM;
+  if (B->criterion != FQ_CRIT_NONE) return FQ_ERR_ENUM;
+  if (A->criterion != FQ_CRIT_NONE && A->criterion != FQ_CRIT_ABSMAX_GT &&
+      A->criterion != FQ_CRIT_ALL)
+    return FQ_ERR_ENUM;
+  const bool a_fb = A->criterion != FQ_CRIT_NONE;
+  if (a_fb && A->capacity == 0) return FQ_ERR_CAPACITY;
+  const int a_nbr = (int)ceil_div(A->rows, FQ_BLOCK), a_nbc = (int)ceil_div(A->cols, FQ_BLOCK);
+  const int b_nbr = (int)ceil_div(B->rows, FQ_BLOCK), b_nbc = (int)ceil_div(B->cols, FQ_BLOCK);
+  *g = fq::GemmParams{};
+  g->a_scales = A->scales;
+  g->a_res_scales = A->res_scales;
+  g->a_slot = a_fb ? A->fb_slot : nullptr;
+  g->b_scales = B->scales;
+  switch (op) {
+    case FQ_OP_NT:  // C[M,N] = A[M,K] B[N,K]^T
+      if (A->cols != B->cols) return FQ_ERR_SHAPE;
+      g->M = A->rows; g->N = B->rows;
+      g->nib = a_nbr; g->njb = b_nbr; g->nkb = a_nbc;
+      g->a_codes = A->codes; g->a_res = A->res_codes; g->a_si = a_nbc; g->a_sk = 1;
+      g->b_codes = B->codes; g->b_sj = b_nbc; g->b_sk = 1;
+      break;
+    case FQ_OP_NN:  // C[M,K] = A[M,N] B[N,K]: B' = B^T
+      if (A->cols != B->rows) return FQ_ERR_SHAPE;
+      if (!B->codes_t) return FQ_ERR_NULL;
+      g->M = A->rows; g->N = B->cols;
+      g->nib = a_nbr; g->njb = b_nbc; g->nkb = a_nbc;
+      g->a_codes = A->codes; g->a_res = A->res_codes; g->a_si = a_nbc; g->a_sk = 1;
+      g->b_codes = B->codes_t; g->b_sj = 1; g->b_sk = b_nbc;
+      break;
+    case FQ_OP_TN:  // C[N,K] = A[M,N]^T B[M,K]: A' = A^T, B' = B^T
+      if (A->rows != B->rows) return FQ_ERR_SHAPE;
+      if (!A->codes_t || !B->codes_t) return FQ_ERR_NULL;
+      if (a_fb && !A->res_codes_t) return FQ_ERR_NULL;
+      g->M = A->cols; g->N = B->cols;
+      g->nib = a_nbc; g->njb = b_nbc; g->nkb = a_nbr;
+      g->a_codes = A->codes_t; g->a_res = A->res_codes_t; g->a_si = 1; g->a_sk = a_nbc;
+      g->b_codes = B->codes_t; g->b_sj = 1; g->b_sk = b_nbc;
+      break;
+  }
+  return FQ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t fq_qtensor_bytes(int32_t rows, int32_t cols, int32_t block, int32_t capacity,
+                        int want_transposed) {
+  Layout L;
+  if (!compute_layout(rows, cols, block, capacity, want_transposed, &L)) return 0;
+  return L.total;
+}
+
+fq_status fq_qtensor_bind(void* base, int32_t rows, int32_t cols, int32_t block,
+                          int32_t capacity, int want_transposed, fq_qtensor* out) {
+  if (!base || !out) return FQ_ERR_NULL;
+  if (block != FQ_BLOCK) return FQ_ERR_BLOCK;
+  Layout L;
+  if (!compute_layout(rows, cols, block, capacity, want_transposed, &L)) return FQ_ERR_SHAPE;
+  if ((uintptr_t)base & 255) return FQ_ERR_SHAPE;
+  char* b = static_cast<char*>(base);
+  out->rows = rows; out->cols = cols; out->block = block; out->capacity = capacity;
+  out->criterion = FQ_CRIT_NONE; out->reserved = 0;
+  out->codes = reinterpret_cast<int8_t*>(b + L.codes);
+  out->codes_t = want_transposed ? reinterpret_cast<int8_t*>(b + L.codes_t) : nullptr;
+  out->scales = reinterpret_cast<float*>(b + L.scales);
+  out->mask = reinterpret_cast<uint8_t*>(b + L.mask);
+  out->fb_count = reinterpret_cast<int32_t*>(b + L.fb_count);
+  out->fb_list = reinterpret_cast<int32_t*>(b + L.fb_list);
+  out->fb_slot = reinterpret_cast<int32_t*>(b + L.fb_slot);
+  out->res_codes = reinterpret_cast<int8_t*>(b + L.res_codes);
+  out->res_codes_t = want_transposed ? reinterpret_cast<int8_t*>(b + L.res_codes_t) : nullptr;
+  out->res_scales = reinterpret_cast<float*>(b + L.res_scales);
+  return FQ_OK;
+}
+
+fq_status fq_quantize(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld, int32_t block,
+                      fq_criterion crit, float theta, fq_qtensor* out, void* hip_stream) {
+  if (!out) return FQ_ERR_NULL;
+  if (block != FQ_BLOCK) return FQ_ERR_BLOCK;
+  if (rows < 0 || cols < 0 || ld < cols) return FQ_ERR_SHAPE;
+  if (crit != FQ_CRIT_NONE && crit != FQ_CRIT_ABSMAX_GT && crit != FQ_CRIT_ALL)
+    return FQ_ERR_ENUM;
+  fq_status s = check_qtensor(out);
+  if (s != FQ_OK) return s;
+  if (out->rows != rows || out->cols != cols) return FQ_ERR_SHAPE;
+  const bool empty = rows == 0 || cols == 0;
+  if (!empty && !x_bf16) return FQ_ERR_NULL;
+  if (crit != FQ_CRIT_NONE && out->capacity == 0 && !empty) return FQ_ERR_CAPACITY;
+
+  fq::QuantParams p{};
+  p.x = static_cast<const uint16_t*>(x_bf16);
+  p.rows = rows; p.cols = cols; p.ld = ld;
+  p.nbr = (int)ceil_div(rows, FQ_BLOCK); p.nbc = (int)ceil_div(cols, FQ_BLOCK);
+  p.vec_ok = (((uintptr_t)x_bf16 & 15) == 0 && (ld % 8) == 0) ? 1 : 0;
+  p.crit = (int)crit; p.theta = theta; p.capacity = out->capacity;
+  p.codes = out->codes; p.codes_t = out->codes_t;
+  p.scales = out->scales; p.mask = out->mask;
+  p.fb_count = out->fb_count; p.fb_list = out->fb_list; p.fb_slot = out->fb_slot;
+  p.res_codes = out->res_codes; p.res_codes_t = out->res_codes_t; p.res_scales = out->res_scales;
+  out->criterion = (int32_t)crit;
+  if (fq::launch_quantize(p, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return FQ_ERR_HIP;
+  return FQ_OK;
+}
+
+fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,
+                  int64_t ldc, void* hip_stream) {
+  fq::GemmParams g;
+  fq_status s = prepare_gemm(op, A, B, &g);
+  if (s != FQ_OK) return s;
+  if (cdt != FQ_OUT_F32 && cdt != FQ_OUT_BF16) return FQ_ERR_ENUM;
+  if (ldc < g.N) return FQ_ERR_SHAPE;
+  if (g.M == 0 || g.N == 0) return FQ_OK;
+  if (!C) return FQ_ERR_NULL;
+  g.c = C; g.ldc = ldc; g.out_bf16 = cdt == FQ_OUT_BF16;
+  if (fq::launch_gemm(g, false, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return FQ_ERR_HIP;
+  return FQ_OK;
+}
+
+fq_status fq_gemm_debug_partials(fq_op op, const fq_qtensor* A, const fq_qtensor* B,
+                                 int32_t k_block, int residual_term, int32_t* p_out,
+                                 void* hip_stream) {
+  fq::GemmParams g;
+  fq_status s = prepare_gemm(op, A, B, &g);
+  if (s != FQ_OK) return s;
+  if (k_block < 0 || k_block >= g.nkb) return FQ_ERR_SHAPE;
+  if (g.M == 0 || g.N == 0) return FQ_OK;
+  if (!p_out) return FQ_ERR_NULL;
+  g.c = p_out; g.ldc = g.N; g.out_bf16 = 0;
+  g.debug_k = k_block; g.debug_residual = residual_term ? 1 : 0;
+  if (fq::launch_gemm(g, true, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return FQ_ERR_HIP;
+  return FQ_OK;
+}
+
+fq_status fq_codes_to_rowmajor(const int8_t* tiled, int32_t rows, int32_t cols, int8_t* dense,
+                               void* hip_stream) {
+  if (rows < 0 || cols < 0) return FQ_ERR_SHAPE;
+  if (rows == 0 || cols == 0) return FQ_OK;
+  if (!tiled || !dense) return FQ_ERR_NULL;
+  if (fq::launch_untile(tiled, rows, cols, dense, static_cast<hipStream_t>(hip_stream)) !=
+      hipSuccess)
+    return FQ_ERR_HIP;
+  return FQ_OK;
+}
+
+fq_status fq_qtensor_check(const fq_qtensor* t, int32_t* count_out, void* hip_stream) {
+  fq_status s = check_qtensor(t);
+  if (s != FQ_OK) return s;
+  int32_t n = 0;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  if (hipMemcpyAsync(&n, t->fb_count, sizeof n, hipMemcpyDeviceToHost, st) != hipSuccess)
+    return FQ_ERR_HIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return FQ_ERR_HIP;
+  if (count_out) *count_out = n;
+  return n > t->capacity ? FQ_ERR_CAPACITY : FQ_OK;
+}
+
+const char* fq_status_string(fq_status s) {
+  switch (s) {
+    case FQ_OK: return "ok";
+    case FQ_ERR_NULL: return "a required pointer is NULL";
+    case FQ_ERR_SHAPE: return "invalid or inconsistent shape";
+    case FQ_ERR_BLOCK: return "unsupported block size (128 only)";
+    case FQ_ERR_ENUM: return "invalid enum value or B operand quantized with fallback";
+    case FQ_ERR_CAPACITY: return "more flagged blocks than residual slots";
+    case FQ_ERR_HIP: return "HIP call failed";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

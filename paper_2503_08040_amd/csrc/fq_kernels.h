@@ -1,0 +1,56 @@
+// Host-visible launch interface between the C ABI layer and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fq {
+
+struct QuantParams {
+  const uint16_t* x;   // bf16 bits, row-major [rows, ld]
+  int rows, cols;
+  int64_t ld;
+  int nbr, nbc;
+  int vec_ok;          // base 16-byte aligned and ld % 8 == 0: full blocks use 16-byte loads
+  int crit;
+  float theta;
+  int capacity;
+  int8_t* codes;
+  int8_t* codes_t;     // nullptr: no transposed copies
+  float* scales;
+  uint8_t* mask;
+  int32_t* fb_count;
+  int32_t* fb_list;
+  int32_t* fb_slot;
+  int8_t* res_codes;
+  int8_t* res_codes_t;
+  float* res_scales;
+};
+
+// The GEMM always runs in "NT on tile-order operands" form: operand A' has
+// nib x nkb blocks, B' has njb x nkb blocks, block (i,k) at (i*nkb + k)*16384.
+// Scales / slots of the stored matrices are reached through strides so that a
+// transposed use (block (i,k) of A' = stored block (k,i)) needs no copy.
+struct GemmParams {
+  const int8_t* a_codes;
+  const int8_t* a_res;        // residual slots (layout matching a_codes' orientation) or nullptr
+  const float* a_scales;
+  const float* a_res_scales;
+  const int32_t* a_slot;      // nullptr: A has no fallback
+  int a_si, a_sk;             // strides of block (i,k) in a_scales / a_slot
+  const int8_t* b_codes;
+  const float* b_scales;
+  int b_sj, b_sk;
+  void* c;                    // [M, ldc] fp32 / bf16, or int32 in debug mode
+  int64_t ldc;
+  int M, N;                   // valid output extent
+  int nib, njb, nkb;
+  int out_bf16;
+  int debug_k;                // debug mode: the single k-block to evaluate
+  int debug_residual;         // debug mode: 0 main term, 1 residual term
+};
+
+hipError_t launch_quantize(const QuantParams& p, hipStream_t st);
+hipError_t launch_untile(const int8_t* tiled, int rows, int cols, int8_t* dense, hipStream_t st);
+hipError_t launch_gemm(const GemmParams& p, bool debug, hipStream_t st);
+
+}  // namespace fq

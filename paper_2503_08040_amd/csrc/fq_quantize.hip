@@ -1,0 +1,253 @@
+// Fused block quantizer: abs-max, INT8 codes, fallback decision, residual
+// quantization and slot allocation in one pass over the bf16 input.
+//
+// Paper: Sec. 3.1 (a = max|G|/127, Q^ = round(G/a)), Sec. 4.4
+// (u = [max|G| > theta]), Sec. 4.3 (second step on the residual G - a Q^),
+// Sec. 5.3 (the fallback decision is fused into the quantization kernel).
+//
+// One 256-thread workgroup owns one 128x128 block (32 KiB of bf16).  Thread t
+// holds 4 rows x 16 consecutive columns in registers: column chunk t%8, rows
+// t/8 + 32*p.  A 16-column chunk is exactly one lane's 16 bytes of a tile-order
+// fragment, so codes leave as 16-byte stores.
+#include "fq_device.h"
+#include "fq_kernels.h"
+
+namespace fq {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+  return v;
+}
+
+// max over the workgroup; every thread gets the result.  red: 4 floats of LDS.
+__device__ inline float block_max(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();  // red may still be read from a previous call
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// round-to-nearest-even of x/a with a correctly rounded division, clamped.
+__device__ inline int quantize_one(float x, float a) {
+  float t = rintf(__fdiv_rn(x, a));
+  t = fminf(fmaxf(t, -127.0f), 127.0f);
+  return (int)t;
+}
+
+__device__ inline v4i pack16(const int* q) {
+  v4i o;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    o[w] = (q[4 * w] & 0xFF) | ((q[4 * w + 1] & 0xFF) << 8) | ((q[4 * w + 2] & 0xFF) << 16) |
+           ((q[4 * w + 3] & 0xFF) << 24);
+  }
+  return o;
+}
+
+// Writes this thread's 4x16 codes into an LDS image of the transposed block in
+// tile order, then the workgroup copies the image out linearly.
+__device__ inline void store_transposed(const int (&q)[4][16], int rp, int cc, int8_t* img,
+                                        int8_t* dst) {
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    int r = p * 32 + rp;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) img[tile_offset(cc * 16 + e, r)] = (int8_t)q[p][e];
+  }
+  __syncthreads();
+  const v4i* src = reinterpret_cast<const v4i*>(img);
+  v4i* out = reinterpret_cast<v4i*>(dst);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) out[i * kThreads + threadIdx.x] = src[i * kThreads + threadIdx.x];
+}
+
+}  // namespace
+
+template <bool kWantT>
+__global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
+  __shared__ float red[4];
+  __shared__ int slot_sh;
+  __shared__ __attribute__((aligned(16))) int8_t img[kWantT ? kBlockBytes : 16];
+
+  const int blk = blockIdx.x;
+  const int bi = blk / p.nbc, bk = blk - bi * p.nbc;
+  const int t = threadIdx.x;
+  const int cc = t & 7, rp = t >> 3;
+  const int row0 = bi * kBlock, col0 = bk * kBlock + cc * 16;
+
+  // ---- load 4 x 16 bf16, zero outside the matrix
+  float x[4][16];
+  const bool inner = (row0 + kBlock <= p.rows) && (bk * kBlock + kBlock <= p.cols) && p.vec_ok;
+  if (inner) {
+#pragma unroll
+    for (int pz = 0; pz < 4; ++pz) {
+      const uint16_t* src = p.x + (int64_t)(row0 + pz * 32 + rp) * p.ld + col0;
+      v4i lo = *reinterpret_cast<const v4i*>(src);
+      v4i hi = *reinterpret_cast<const v4i*>(src + 8);
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        x[pz][2 * w] = bf16_bits_to_float((uint32_t)lo[w] & 0xFFFFu);
+        x[pz][2 * w + 1] = __uint_as_float((uint32_t)lo[w] & 0xFFFF0000u);
+        x[pz][8 + 2 * w] = bf16_bits_to_float((uint32_t)hi[w] & 0xFFFFu);
+        x[pz][8 + 2 * w + 1] = __uint_as_float((uint32_t)hi[w] & 0xFFFF0000u);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int pz = 0; pz < 4; ++pz) {
+      const int r = row0 + pz * 32 + rp;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int c = col0 + e;
+        x[pz][e] = (r < p.rows && c < p.cols)
+                       ? bf16_bits_to_float(p.x[(int64_t)r * p.ld + c]) : 0.0f;
+      }
+    }
+  }
+
+  // ---- step 1: a = max|G| / 127, codes = round(G / a)           (Sec. 3.1)
+  float m = 0.0f;
+#pragma unroll
+  for (int pz = 0; pz < 4; ++pz)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) m = fmaxf(m, fabsf(x[pz][e]));
+  const float amax = block_max(m, red);
+  const float a = __fdiv_rn(amax, 127.0f);
+
+  int q[4][16];
+#pragma unroll
+  for (int pz = 0; pz < 4; ++pz)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) q[pz][e] = (a == 0.0f) ? 0 : quantize_one(x[pz][e], a);
+
+  int8_t* cdst = p.codes + (int64_t)blk * kBlockBytes;
+#pragma unroll
+  for (int pz = 0; pz < 4; ++pz)
+    *reinterpret_cast<v4i*>(cdst + tile_offset(pz * 32 + rp, cc * 16)) = pack16(q[pz]);
+  if (kWantT)
+    store_transposed(q, rp, cc, img, p.codes_t + ((int64_t)bk * p.nbr + bi) * kBlockBytes);
+
+  // ---- fallback decision                                         (Sec. 4.4)
+  bool u;
+  if (p.crit == 0) u = false;
+  else if (p.crit == 2) u = true;
+  else u = amax > p.theta;
+
+  int slot = -1;
+  if (u) {
+    if (t == 0) {
+      int s = atomicAdd(p.fb_count, 1);
+      slot_sh = (s < p.capacity) ? s : -2;
+    }
+    __syncthreads();
+    slot = slot_sh;
+  }
+  if (t == 0) {
+    p.scales[blk] = a;
+    p.mask[blk] = u ? 1 : 0;
+    p.fb_slot[blk] = slot;
+  }
+  if (slot < 0) return;  // uniform over the workgroup
+
+  // ---- step 2: quantize the residual G - a*codes                 (Sec. 4.3)
+  float rm = 0.0f;
+#pragma unroll
+  for (int pz = 0; pz < 4; ++pz)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      x[pz][e] = __builtin_fmaf(-(float)q[pz][e], a, x[pz][e]);
+      rm = fmaxf(rm, fabsf(x[pz][e]));
+    }
+  const float rmax = block_max(rm, red);
+  const float ra = __fdiv_rn(rmax, 127.0f);
+#pragma unroll
+  for (int pz = 0; pz < 4; ++pz)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) q[pz][e] = (ra == 0.0f) ? 0 : quantize_one(x[pz][e], ra);
+
+  int8_t* rdst = p.res_codes + (int64_t)slot * kBlockBytes;
+#pragma unroll
+  for (int pz = 0; pz < 4; ++pz)
+    *reinterpret_cast<v4i*>(rdst + tile_offset(pz * 32 + rp, cc * 16)) = pack16(q[pz]);
+  if (kWantT) store_transposed(q, rp, cc, img, p.res_codes_t + (int64_t)slot * kBlockBytes);
+  if (t == 0) p.res_scales[slot] = ra;
+}
+
+// fb_count = 0 before the quantizer allocates slots with it.
+__global__ void zero_count_kernel(int32_t* fb_count) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) *fb_count = 0;
+}
+
+// Ascending list of flagged block ids from the mask (one workgroup, any size).
+__global__ __launch_bounds__(1024) void fb_list_kernel(const uint8_t* mask, int n, int32_t* list) {
+  __shared__ int wsum[16];
+  __shared__ int base_sh;
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  if (t == 0) base_sh = 0;
+  __syncthreads();
+  for (int start = 0; start < n; start += 1024) {
+    const int i = start + t;
+    const int f = (i < n && mask[i]) ? 1 : 0;
+    // inclusive scan inside the wave
+    int s = f;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      int v = __shfl_up(s, off, 64);
+      if (lane >= off) s += v;
+    }
+    if (lane == 63) wsum[w] = s;
+    __syncthreads();
+    int before = base_sh;
+    for (int j = 0; j < w; ++j) before += wsum[j];
+    if (f) list[before + s - 1] = i;
+    __syncthreads();
+    if (t == 0) {
+      int tot = 0;
+      for (int j = 0; j < 16; ++j) tot += wsum[j];
+      base_sh += tot;
+    }
+    __syncthreads();
+  }
+  const int total = base_sh;
+  for (int i = total + t; i < n; i += 1024) list[i] = -1;
+}
+
+// Tile order -> dense row-major (inspection / tests).
+__global__ void untile_kernel(const int8_t* tiled, int rows, int cols, int nbc, int8_t* dense) {
+  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (int64_t)rows * cols) return;
+  const int r = (int)(idx / cols), c = (int)(idx - (int64_t)r * cols);
+  const int64_t blk = (int64_t)(r >> 7) * nbc + (c >> 7);
+  dense[idx] = tiled[blk * kBlockBytes + tile_offset(r & 127, c & 127)];
+}
+
+hipError_t launch_quantize(const QuantParams& p, hipStream_t st) {
+  hipLaunchKernelGGL(zero_count_kernel, dim3(1), dim3(64), 0, st, p.fb_count);
+  const int nb = p.nbr * p.nbc;
+  if (nb > 0) {
+    if (p.codes_t)
+      hipLaunchKernelGGL(quantize_kernel<true>, dim3(nb), dim3(kThreads), 0, st, p);
+    else
+      hipLaunchKernelGGL(quantize_kernel<false>, dim3(nb), dim3(kThreads), 0, st, p);
+    hipLaunchKernelGGL(fb_list_kernel, dim3(1), dim3(1024), 0, st, p.mask, nb, p.fb_list);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_untile(const int8_t* tiled, int rows, int cols, int8_t* dense, hipStream_t st) {
+  const int64_t n = (int64_t)rows * cols;
+  if (n == 0) return hipSuccess;
+  const int nbc = (cols + kBlock - 1) / kBlock;
+  hipLaunchKernelGGL(untile_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, tiled,
+                     rows, cols, nbc, dense);
+  return hipGetLastError();
+}
+
+}  // namespace fq

@@ -1,0 +1,201 @@
+"""GPU parity: fq_gemm / fq_gemm_debug_partials against the CPU oracle.
+
+INT32 block products must match bit for bit.  FP32 outputs must be within
+1e-3 (max |diff| / max |ref|); because the kernel keeps Alg. 1's accumulation
+order they are in fact expected to be identical, which is asserted too.
+bf16 outputs may differ by one bf16 ulp only where the fp32 values differ."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2503_08040_amd as fq
+from oracle import fqo
+from paper_2503_08040_amd import synth
+from tests import gpu_util as gu
+
+F32 = np.float32
+TOL = 1e-3
+
+
+def _quant_pair(a_bits, b_bits, crit, theta):
+    ga = fq.fq_quantize(gu.to_device_bf16(a_bits), crit, theta, want_transposed=True)
+    gb = fq.fq_quantize(gu.to_device_bf16(b_bits), fq.FQ_CRIT_NONE, 0.0, want_transposed=True)
+    oa = fqo.quantize(a_bits, 128, crit, theta)
+    ob = fqo.quantize(b_bits, 128, fqo.CRIT_NONE, 0.0)
+    return ga, gb, oa, ob
+
+
+def _check_gemm(op, ga, gb, oa, ob, label, partials=True, exact_ref=None):
+    Mo, No = fqo.out_shape(op, oa, ob)
+    nkb = -(-(oa.rows if op == fqo.OP_TN else oa.cols) // 128)
+    if partials:
+        for kb in range(nkb):
+            for res in (False, True):
+                gu.announce(f"{label}: partials op={op} kb={kb} res={res}")
+                gp = fq.fq_gemm_debug_partials(op, ga, gb, kb, res).cpu().numpy()
+                op_ = fqo.gemm_partials(op, oa, ob, kb, res)
+                assert np.array_equal(gp, op_), f"{label}: INT32 partials kb={kb} res={res}"
+    gu.announce(f"{label}: gemm op={op} fp32")
+    ref, refb = fqo.gemm(op, oa, ob, want_bf16=True)
+    c = fq.fq_gemm(op, ga, gb).cpu().numpy()
+    assert c.shape == (Mo, No)
+    err = gu.rel_err(c, ref)
+    assert err <= TOL, f"{label}: rel err {err}"
+    assert np.array_equal(c, ref), f"{label}: fp32 output not bit-identical (rel err {err})"
+    gu.announce(f"{label}: gemm op={op} bf16")
+    cb = fq.fq_gemm(op, ga, gb, out_dtype=torch.bfloat16).view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(cb, refb), f"{label}: bf16 output differs"
+    if exact_ref is not None:
+        e64 = gu.rel_err(c, exact_ref)
+        print(f"{label}: error vs exact fp64 GEMM {e64:.3e}", flush=True)
+        assert e64 < 0.1     # accuracy of the method itself (INT8 blocks), informational
+    return c
+
+
+def test_config1_forward():
+    wl = synth.config1()
+    ga, gb, oa, ob = _quant_pair(wl.X, wl.W, fq.FQ_CRIT_ABSMAX_GT, wl.theta)
+    exact = synth.bf16_bits_to_f32(wl.X).astype(np.float64) @ synth.bf16_bits_to_f32(wl.W).astype(np.float64).T
+    c = _check_gemm(fq.FQ_OP_NT, ga, gb, oa, ob, "cfg1", exact_ref=exact)
+    # fallback visibly helps: the plain block-INT8 product is farther from the exact one
+    gn = fq.fq_quantize(gu.to_device_bf16(wl.X), fq.FQ_CRIT_NONE, 0.0)
+    cn = fq.fq_gemm(fq.FQ_OP_NT, gn, gb).cpu().numpy()
+    on = fqo.quantize(wl.X, 128, fqo.CRIT_NONE, 0.0)
+    assert np.array_equal(cn, fqo.gemm(fqo.OP_NT, on, ob))
+    rows = slice(128, 256)
+    assert np.abs(cn[rows] - exact[rows]).mean() > 3 * np.abs(c[rows] - exact[rows]).mean()
+
+
+def test_config1_full_fallback_and_none():
+    wl = synth.config1()
+    for crit in (fq.FQ_CRIT_ALL, fq.FQ_CRIT_NONE):
+        ga, gb, oa, ob = _quant_pair(wl.X, wl.W, crit, 0.0)
+        _check_gemm(fq.FQ_OP_NT, ga, gb, oa, ob, f"cfg1 crit={crit}", partials=False)
+
+
+def test_config4_backward():
+    wl = synth.config4()
+    dy, w, x = wl.dY, wl.W, wl.X
+    f64 = lambda b: synth.bf16_bits_to_f32(b).astype(np.float64)
+    ga, gb, oa, ob = _quant_pair(dy, w, fq.FQ_CRIT_ABSMAX_GT, wl.theta)
+    assert int(oa.fb_count[0]) == 2
+    _check_gemm(fq.FQ_OP_NN, ga, gb, oa, ob, "cfg4 dX", exact_ref=f64(dy) @ f64(w))
+    ga, gx, oa, ox = _quant_pair(dy, x, fq.FQ_CRIT_ABSMAX_GT, wl.theta)
+    _check_gemm(fq.FQ_OP_TN, ga, gx, oa, ox, "cfg4 dW", exact_ref=f64(dy).T @ f64(x))
+
+
+@pytest.mark.parametrize("op,sa,sb", [
+    (fq.FQ_OP_NT, (130, 200), (77, 200)),
+    (fq.FQ_OP_NT, (300, 513), (260, 513)),
+    (fq.FQ_OP_NT, (1, 1), (1, 1)),
+    (fq.FQ_OP_NN, (130, 200), (200, 77)),
+    (fq.FQ_OP_NN, (257, 384), (384, 300)),
+    (fq.FQ_OP_TN, (200, 130), (200, 77)),
+    (fq.FQ_OP_TN, (384, 257), (384, 300)),
+    (fq.FQ_OP_NT, (640, 384), (768, 384)),
+])
+def test_ragged_and_multi_tile_shapes(op, sa, sb):
+    rng = np.random.default_rng(sa[0] + 7 * sb[1] + op)
+    a = rng.standard_normal(sa).astype(F32)
+    for _ in range(4):
+        a[rng.integers(sa[0]), rng.integers(sa[1])] *= 120.0
+    b = rng.standard_normal(sb).astype(F32) * F32(0.02)
+    ga, gb, oa, ob = _quant_pair(synth.to_bf16_bits(a), synth.to_bf16_bits(b),
+                                 fq.FQ_CRIT_ABSMAX_GT, 8.0)
+    _check_gemm(op, ga, gb, oa, ob, f"ragged op={op} {sa}x{sb}", partials=(sa[0] <= 300))
+
+
+def test_strided_output_and_reuse():
+    wl = synth.config1()
+    ga, gb, oa, ob = _quant_pair(wl.X, wl.W, fq.FQ_CRIT_ABSMAX_GT, wl.theta)
+    ref = fqo.gemm(fqo.OP_NT, oa, ob)
+    big = torch.full((256, 600), 7.0, device="cuda")
+    gu.announce("gemm into a strided output view")
+    fq.fq_gemm(fq.FQ_OP_NT, ga, gb, out=big[:, 40:552])
+    out = big.cpu().numpy()
+    assert np.array_equal(out[:, 40:552], ref)
+    assert np.all(out[:, :40] == 7.0) and np.all(out[:, 552:] == 7.0)
+    gu.announce("gemm twice: deterministic")
+    c1 = fq.fq_gemm(fq.FQ_OP_NT, ga, gb)
+    c2 = fq.fq_gemm(fq.FQ_OP_NT, ga, gb)
+    assert torch.equal(c1, c2)
+
+
+def test_empty_contraction_and_empty_output():
+    a = fq.fq_quantize(torch.empty((256, 0), dtype=torch.bfloat16, device="cuda"),
+                       fq.FQ_CRIT_NONE, 0.0, capacity=0)
+    b = fq.fq_quantize(torch.empty((128, 0), dtype=torch.bfloat16, device="cuda"),
+                       fq.FQ_CRIT_NONE, 0.0, capacity=0)
+    gu.announce("gemm with K = 0")
+    c = fq.fq_gemm(fq.FQ_OP_NT, a, b, out=torch.full((256, 128), 3.0, device="cuda"))
+    assert torch.count_nonzero(c).item() == 0
+    a0 = fq.fq_quantize(torch.empty((0, 256), dtype=torch.bfloat16, device="cuda"),
+                        fq.FQ_CRIT_NONE, 0.0, capacity=0)
+    b0 = fq.fq_quantize(torch.zeros((128, 256), dtype=torch.bfloat16, device="cuda"),
+                        fq.FQ_CRIT_NONE, 0.0, capacity=0)
+    gu.announce("gemm with M = 0")
+    assert fq.fq_gemm(fq.FQ_OP_NT, a0, b0).shape == (0, 128)
+
+
+def test_capacity_overflow_poisons_output():
+    wl = synth.config1()
+    x = gu.to_device_bf16(wl.X)
+    gb = fq.fq_quantize(gu.to_device_bf16(wl.W), fq.FQ_CRIT_NONE, 0.0)
+    ga = fq.fq_quantize(x, fq.FQ_CRIT_ALL, 0.0, capacity=3)
+    gu.announce("gemm on a tensor whose residual slots overflowed")
+    c = fq.fq_gemm(fq.FQ_OP_NT, ga, gb)
+    assert torch.isnan(c).any().item()      # never a silently wrong product
+
+
+def _sampled_windows(rng, Mo, No, flagged_rows, n=24, h=4, w=8):
+    wins = []
+    rows = list(flagged_rows[:n // 2]) + list(rng.integers(0, Mo - h, size=n - len(flagged_rows[:n // 2])))
+    for r in rows:
+        r = int(min(max(r, 0), Mo - h))
+        c = int(rng.integers(0, No - w))
+        wins.append((r, r + h, c, c + w))
+    wins.append((Mo - h, Mo, No - w, No))
+    wins.append((0, h, 0, w))
+    return wins
+
+
+@pytest.mark.parametrize("cfg", ["cfg2", "cfg3", "cfg5_random", "cfg5_sequential"])
+def test_full_size_sampled(cfg):
+    """BASELINE configs 2, 3 and 5 at full size, in the launch configuration the
+    benchmark times: quantizer outputs bit-exact in full, GEMM outputs compared
+    on sampled windows the oracle computes element by element (windows cover
+    every kind of row: with flagged blocks, without, first and last tile)."""
+    wl = {"cfg2": lambda: synth.config2(), "cfg3": lambda: synth.config3(),
+          "cfg5_random": lambda: synth.config5(frac=0.05, placement="random"),
+          "cfg5_sequential": lambda: synth.config5(frac=0.05, placement="sequential")}[cfg]()
+    gu.announce(f"{cfg}: quantize X {wl.X.shape} / W {wl.W.shape}")
+    ga = fq.fq_quantize(gu.to_device_bf16(wl.X), fq.FQ_CRIT_ABSMAX_GT, wl.theta)
+    gb = fq.fq_quantize(gu.to_device_bf16(wl.W), fq.FQ_CRIT_NONE, 0.0, capacity=0)
+    oa = fqo.quantize(wl.X, 128, fqo.CRIT_ABSMAX_GT, wl.theta)
+    ob = fqo.quantize(wl.W, 128, fqo.CRIT_NONE, 0.0)
+    assert np.array_equal(oa.fb_list[:oa.fb_count[0]], wl.flagged_blocks)
+    gu.compare_quantized(ga, oa, f"{cfg} X")
+    gu.compare_quantized(gb, ob, f"{cfg} W")
+    gu.announce(f"{cfg}: gemm")
+    c = fq.fq_gemm(fq.FQ_OP_NT, ga, gb, out_dtype=torch.bfloat16)
+    c32 = fq.fq_gemm(fq.FQ_OP_NT, ga, gb)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(0)
+    nbc = oa.nbc
+    frows = sorted({(int(b) // nbc) * 128 + int(rng.integers(0, 124)) for b in wl.flagged_blocks})
+    rng.shuffle(frows)
+    worst = 0.0
+    for (i0, i1, j0, j1) in _sampled_windows(rng, wl.M, wl.N, frows):
+        ref, refb = fqo.gemm(fqo.OP_NT, oa, ob, window=(i0, i1, j0, j1), want_bf16=True)
+        got = c32[i0:i1, j0:j1].cpu().numpy()
+        worst = max(worst, gu.rel_err(got, ref[i0:i1, j0:j1]))
+        assert np.array_equal(got, ref[i0:i1, j0:j1]), f"{cfg}: window {(i0, i1, j0, j1)}"
+        gotb = c[i0:i1, j0:j1].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        assert np.array_equal(gotb, refb[i0:i1, j0:j1])
+    assert worst <= TOL
+    # properties that hold at any size: finite everywhere, bf16 output is the rounding of fp32
+    assert torch.isfinite(c32).all().item()
+    assert torch.equal(c, c32.to(torch.bfloat16))
