@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the Fallback-Quantization hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch: fq_quantize of
+the activation X (block abs-max, INT8 codes, fallback decision, residual
+quantization, compaction) followed by fq_gemm Y = X W^T on the INT8 matrix
+cores with the fallback term.  The weight is quantized once before timing (its
+cost is reported separately).  Inputs are resident in HBM when timing starts.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0     # MI355X dense INT8 MFMA peak (published), TOP/s
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def make_workload(name):
+    from paper_2503_08040_amd import synth
+    if name == "cfg1":
+        return synth.config1()
+    if name == "cfg2":
+        return synth.config2()
+    if name == "cfg3":
+        return synth.config3()
+    if name.startswith("cfg5"):
+        parts = name.split(":")
+        frac = float(parts[1]) if len(parts) > 1 else 0.05
+        placement = parts[2] if len(parts) > 2 else "random"
+        return synth.config5(frac=frac, placement=placement)
+    raise SystemExit(f"unknown workload {name}")
+
+
+def cpu_baseline(wl, budget_s=15.0):
+    """Times the CPU oracle (as it stands) on a bounded window of the same workload."""
+    from oracle import fqo
+    rows = min(wl.M, 1024)
+    t0 = time.perf_counter()
+    oa = fqo.quantize(wl.X[:rows], 128, fqo.CRIT_ABSMAX_GT, wl.theta)
+    tq = time.perf_counter() - t0
+    ob = fqo.quantize(wl.W, 128, fqo.CRIT_NONE, 0.0)
+    # calibrate on a small window, then size the timed window to the budget
+    cols = min(wl.N, 64)
+    t0 = time.perf_counter()
+    fqo.gemm(fqo.OP_NT, oa, ob, window=(0, rows, 0, cols))
+    tc = time.perf_counter() - t0
+    scale = max(1.0, min(budget_s / max(tc, 1e-3), wl.N / cols))
+    cols2 = int(min(wl.N, cols * scale)) // 64 * 64 or cols
+    t0 = time.perf_counter()
+    fqo.gemm(fqo.OP_NT, oa, ob, window=(0, rows, 0, cols2))
+    tg = time.perf_counter() - t0
+    # quantizing these rows of X is shared by all N columns: charge the window's share
+    tq_share = tq * cols2 / wl.N
+    ops = 2.0 * rows * cols2 * wl.K
+    return {"value": ops / (tg + tq_share) / 1e12, "unit": "TOPS", "cores": fqo.num_threads(),
+            "kind": "oracle",
+            "sample": f"oracle fqo_quantize on X[0:{rows}] + fqo_gemm on the {rows}x{cols2} output "
+                      f"window (K={wl.K}); {tg:.2f}s gemm + {tq_share:.3f}s quantize share"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg2",
+                    help="cfg2 (default, GLU up/gate 4096x4096x11008), cfg3, cfg1, cfg5[:frac[:placement]]")
+    ap.add_argument("--out-dtype", default="bf16", choices=["bf16", "f32"])
+    ap.add_argument("--warmup-seconds", type=float, default=1.5,
+                    help="minimum duration of the untimed warm-up (clock ramp)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bf16-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path "
+                         "(run with --gpus 1)")
+
+    import torch
+    import paper_2503_08040_amd as fq
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    log(f"[bench] generating {args.workload}")
+    wl = make_workload(args.workload)
+    M, K, N = wl.M, wl.K, wl.N
+    x = torch.from_numpy(wl.X.view(np.int16)).cuda().view(torch.bfloat16)
+    w = torch.from_numpy(wl.W.view(np.int16)).cuda().view(torch.bfloat16)
+    out_dtype = torch.bfloat16 if args.out_dtype == "bf16" else torch.float32
+    y = torch.empty((M, N), dtype=out_dtype, device="cuda")
+
+    qx = fq.QTensor(M, K)
+    qw = fq.QTensor(N, K, capacity=0)
+    fq.fq_quantize(w, fq.FQ_CRIT_NONE, 0.0, out=qw)
+    fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, wl.theta, out=qx)
+    n_fb = fq.fq_qtensor_check(qx)
+    f = n_fb / (qx.nbr * qx.nbc)
+    log(f"[bench] M={M} K={K} N={N} flagged blocks {n_fb} ({100 * f:.2f} %)")
+
+    def step():
+        fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, wl.theta, out=qx)
+        fq.fq_gemm(fq.FQ_OP_NT, qx, qw, out=y)
+
+    # Warm-up: at least W steps and at least --warmup-seconds of back-to-back work, because the
+    # GPU needs a few hundred milliseconds of load to leave its idle clock state.
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t_w = time.perf_counter()
+    while time.perf_counter() - t_w < args.warmup_seconds:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, wl.theta, out=qx)
+        ev[i][1].record()
+        fq.fq_gemm(fq.FQ_OP_NT, qx, qw, out=y)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    ms_quant = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    ms_gemm = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+
+    ops = 2.0 * M * N * K
+    value = ops / (ms_step * 1e-3) / 1e12
+    gemm_alg_ops = ops * (1.0 + f)          # the residual products are real MFMA work
+    achieved = gemm_alg_ops / (ms_gemm * 1e-3) / 1e12
+    quant_bytes = (3.0 + f) * M * K + 9.0 * qx.nbr * qx.nbc
+    result = {
+        "metric": "effective TOPS of quantize+fallback GEMM (% INT8 MFMA peak) vs bf16 GEMM, 1 GPU",
+        "value": round(value, 2), "unit": "TOPS", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
+        "config": {"workload": wl.name, "M": M, "K": K, "N": N, "block": 128,
+                   "fallback_fraction": round(f, 5), "theta": wl.theta, "out_dtype": args.out_dtype,
+                   "step": "fq_quantize(X) + fq_gemm(NT); W pre-quantized"},
+        "pct_int8_peak": round(100.0 * value / INT8_PEAK_TOPS, 2),
+        "ms_quantize": round(ms_quant, 5), "ms_gemm": round(ms_gemm, 5),
+        "gemm_only_tops": round(ops / (ms_gemm * 1e-3) / 1e12, 2),
+        "quantizer_gbs": round(quant_bytes / (ms_quant * 1e-3) / 1e9, 1),
+        "roofline": {"bound": "mfma", "kernel": "fq::gemm_kernel<false>",
+                     "achieved": round(achieved, 2), "peak": INT8_PEAK_TOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": None,
+                     "note": "INT8 ops: 2*M*N*K*(1+f) per launch / HIP-event time of fq_gemm"},
+    }
+
+    # weight quantization (once per optimizer step in training), reported separately
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(3):
+        fq.fq_quantize(w, fq.FQ_CRIT_NONE, 0.0, out=qw)
+    e0.record()
+    for _ in range(10):
+        fq.fq_quantize(w, fq.FQ_CRIT_NONE, 0.0, out=qw)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_wq = e0.elapsed_time(e1) / 10
+    result["ms_quantize_weight"] = round(ms_wq, 5)
+    result["tops_incl_weight_quant"] = round(ops / ((ms_step + ms_wq) * 1e-3) / 1e12, 2)
+
+    if not args.no_bf16_baseline:
+        yb = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        t_w = time.perf_counter()
+        while time.perf_counter() - t_w < min(args.warmup_seconds, 1.0):
+            for _ in range(10):
+                torch.matmul(x, w.t(), out=yb)
+            torch.cuda.synchronize()
+        e0.record()
+        for _ in range(50):
+            torch.matmul(x, w.t(), out=yb)
+        e1.record()
+        torch.cuda.synchronize()
+        ms_bf16 = e0.elapsed_time(e1) / 50
+        result["bf16_gemm"] = {"impl": "torch.matmul (hipBLASLt)", "ms": round(ms_bf16, 5),
+                               "tflops": round(ops / (ms_bf16 * 1e-3) / 1e12, 2),
+                               "speedup_of_fq": round(ms_bf16 / ms_step, 3)}
+
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a bounded sample")
+        result["cpu_baseline"] = cpu_baseline(wl)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

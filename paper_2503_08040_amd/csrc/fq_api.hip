@@ -172,6 +172,8 @@ fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, f
   if (g.M == 0 || g.N == 0) return FQ_OK;
   if (!C) return FQ_ERR_NULL;
   g.c = C; g.ldc = ldc; g.out_bf16 = cdt == FQ_OUT_BF16;
+  const int64_t esz = g.out_bf16 ? 2 : 4;
+  g.vec_ok = (((uintptr_t)C & 15) == 0 && (ldc * esz) % 16 == 0) ? 1 : 0;
   if (fq::launch_gemm(g, false, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return FQ_ERR_HIP;
   return FQ_OK;
@@ -187,6 +189,7 @@ fq_status fq_gemm_debug_partials(fq_op op, const fq_qtensor* A, const fq_qtensor
   if (g.M == 0 || g.N == 0) return FQ_OK;
   if (!p_out) return FQ_ERR_NULL;
   g.c = p_out; g.ldc = g.N; g.out_bf16 = 0;
+  g.vec_ok = (((uintptr_t)p_out & 15) == 0 && (g.N % 4) == 0) ? 1 : 0;
   g.debug_k = k_block; g.debug_residual = residual_term ? 1 : 0;
   if (fq::launch_gemm(g, true, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return FQ_ERR_HIP;

@@ -38,54 +38,179 @@ namespace fq {
 namespace {
 
 constexpr int kThreads = 512;
+constexpr int kXcds = 8;      // accelerator complex dies, each with a private L2
+constexpr int kGroupM = 4;    // tile rows per rasterization group
 constexpr int kRingBytes = 2 * kBlockBytes;     // one A pair or one B pair
-constexpr int kLdsBytes = 4 * kRingBytes;       // A ring x2, B ring x2 = 128 KiB
+constexpr int kStagePitch = 72;                 // floats per row of the epilogue staging patch
+constexpr int kStageBytesPerWave = 64 * kStagePitch * 4;
+constexpr int kLdsBytes = 8 * kStageBytesPerWave;   // 144 KiB: covers the rings (A x2, B x2 = 128 KiB)
+static_assert(kLdsBytes >= 4 * kRingBytes, "LDS must hold both operand rings");
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void gbl_void;
 
-// One wavefront copies 8 KiB (8 fragments) global -> LDS with direct loads.
+// One wavefront copies 8 KiB (8 fragments) global -> LDS with direct loads.  `src` and
+// `lds_dst` are wave-uniform; the per-lane part of the address is the 32-bit offset lane*16,
+// so the loads use the scalar-base addressing form and need no 64-bit address registers.
 __device__ inline void stage_half_block(const int8_t* src, int8_t* lds_dst, int lane) {
+  const unsigned voff = (unsigned)lane * 16u;
 #pragma unroll
   for (int f = 0; f < 8; ++f) {
-    __builtin_amdgcn_global_load_lds((gbl_void*)(src + f * kFragBytes + lane * 16),
+    __builtin_amdgcn_global_load_lds((gbl_void*)(src + f * kFragBytes + voff),
                                      (lds_void*)(lds_dst + f * kFragBytes), 16, 0, 0);
   }
+}
+
+// two floats -> two bf16 (round-to-nearest-even) in one dword, low half first
+__device__ inline int pack_bf16x2(float a, float b) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  f32x2 v = {a, b};
+  return __builtin_bit_cast(int, __builtin_convertvector(v, bf16x2));
 }
 
 __device__ inline v4i lds_frag(const int8_t* blk, int rg, int ks, int lane) {
   return *reinterpret_cast<const v4i*>(blk + ((rg * 4 + ks) * 64 + lane) * 16);
 }
 
+
+// Empty volatile asm statements that take values as read-write register operands.  The
+// compiler may not reorder volatile asm, so the instructions producing the operands stay
+// before the statement and their consumers after it: this pins the source order of otherwise
+// freely movable pure instructions (MFMA, convert, FMA) without emitting any code.
+__device__ __forceinline__ void pin(v16i& x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void pin(float& a, float& b, float& c, float& d) {
+  asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+
+// Per-wavefront register state of the k-loop.
+struct WaveState {
+  float acc[4][2][16];   // FP32 accumulators: sub-tile (si, sj), 16 elements per lane
+  v4i aq[4];             // A fragments of the current si (ks = 0..3)
+  v4i bq[2][4];          // B fragments of this wave's two column groups
+  v16i P[2];             // INT32 tiles: sub-tile u accumulates into P[u & 1]
+  float T[4];            // elements converted in the previous slot, waiting for their FMA
+};
+
+// The k-loop is one continuous software pipeline over sub-tiles ("units": u = 2*si + sj, 8 per
+// item).  Unit u is 4 slots; slot g issues MFMA g (K = 32 of the 128) of unit u and, in the 32
+// cycles the matrix core needs for it, 8 vector-ALU instructions that fold the finished INT32
+// tile of unit u-1 into the FP32 accumulators: the 4 FMAs of the elements converted one slot
+// earlier, then 4 converts of elements 4g..4g+3 (an FMA never waits for its convert, and a
+// convert reads an MFMA result that is at least 11 issue slots old, as the hardware requires).
+// Fragment registers are refilled from LDS right after their last use: A fragments of the next
+// si inside the item, and in units 6 and 7 the B fragments and first A fragments of the NEXT
+// item, so that no item starts with a burst of LDS reads.  Scheduling fences pin this order.
+//   a_cur: A pair of the current item in LDS; a_nxt / b_nxt: A pair / B block of the next item.
+//   s0, s1: scales of the current item's two i-blocks; sp: scale of the previous item's si = 3.
+template <int u>
+__device__ __forceinline__ void run_unit(WaveState& st, const int8_t* a_cur, const int8_t* a_nxt,
+                                         const int8_t* b_nxt, int h, int jq, int lane, float s0,
+                                         float s1, float sp) {
+  constexpr int si = u >> 1, sj = u & 1;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    {
+      const v16i z = {0};
+      st.P[u & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(st.aq[g], st.bq[sj][g],
+                                                          g ? st.P[u & 1] : z, 0, 0, 0);
+      if (u < 6 && sj == 1)
+        st.aq[g] = lds_frag(a_cur + ((si + 1) >> 1) * kBlockBytes, 2 * h + ((si + 1) & 1), g, lane);
+      if (u == 6) st.bq[0][g] = lds_frag(b_nxt, 2 * (jq & 1), g, lane);
+      if (u == 7) {
+        st.bq[1][g] = lds_frag(b_nxt, 2 * (jq & 1) + 1, g, lane);
+        st.aq[g] = lds_frag(a_nxt, 2 * h, g, lane);
+      }
+      pin(st.P[u & 1]);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // MFMA first: its destination must not alias live tiles
+    {
+      // FMAs of the 4 elements converted in the previous slot (unit u-1, or u-2 for g = 0);
+      // negative units are units 6, 7 of the previous item (si = 3)
+      const int fu = g ? u - 1 : u - 2, fc = g ? g - 1 : 3;
+      const int fsi = fu < 0 ? 3 : (fu >> 1), fsj = fu & 1;
+      const float s = fu < 0 ? sp : (fsi < 2 ? s0 : s1);
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        st.acc[fsi][fsj][4 * fc + i] = __builtin_fmaf(st.T[i], s, st.acc[fsi][fsj][4 * fc + i]);
+      pin(st.acc[fsi][fsj][4 * fc], st.acc[fsi][fsj][4 * fc + 1], st.acc[fsi][fsj][4 * fc + 2],
+          st.acc[fsi][fsj][4 * fc + 3]);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // FMAs before converts
+#pragma unroll
+    for (int i = 0; i < 4; ++i) st.T[i] = (float)st.P[(u - 1) & 1][4 * g + i];
+    pin(st.T[0], st.T[1], st.T[2], st.T[3]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Folds the last unit (si = 3, sj = 1) of the last item into the accumulators.
+__device__ __forceinline__ void drain(WaveState& st, float s1) {
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const int fsj = g ? 1 : 0, fc = g ? g - 1 : 3;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      st.acc[3][fsj][4 * fc + i] = __builtin_fmaf(st.T[i], s1, st.acc[3][fsj][4 * fc + i]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) st.T[i] = (float)st.P[1][4 * g + i];
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) st.acc[3][1][12 + i] = __builtin_fmaf(st.T[i], s1, st.acc[3][1][12 + i]);
+}
+
+// Scalars of one k-block: residual slots and scales of the tile's two A blocks, scale of this
+// wave's B block.
+struct KRec {
+  int slot0, slot1;
+  float sa0, sa1, sb;
+};
+
 }  // namespace
 
-template <bool kDebug>
 __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
   int8_t* const a_ring = lds;                   // [2][2 blocks]
   int8_t* const b_ring = lds + 2 * kRingBytes;  // [2][2 blocks]
+  constexpr bool kDebug = false;
 
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int h = w >> 2, jq = w & 3;
 
-  // ---- tile of this workgroup; out-of-range blocks repeat the last valid one (never stored)
-  const int tiles_j = (p.njb + 1) >> 1;
-  const int ti = blockIdx.x / tiles_j, tj = blockIdx.x - ti * tiles_j;
+  // ---- tile of this workgroup; out-of-range blocks repeat the last valid one (never stored).
+  // Workgroups are dealt to the 8 XCDs round-robin by id, and each XCD has its own L2.  Remap
+  // ids so that one XCD works through a contiguous run of tiles, and order the tiles in groups
+  // of kGroupM tile-rows walked column by column: the ~32 tiles resident on an XCD then form a
+  // 4 x 8 patch that shares its A and B blocks through that L2.
+  const int tiles_i = (p.nib + 1) >> 1, tiles_j = (p.njb + 1) >> 1;
+  int ti, tj;
+  {
+    const int total = tiles_i * tiles_j;
+    const int b = blockIdx.x, xcd = b % kXcds, l = b / kXcds;
+    const int q = total / kXcds, rem = total % kXcds;
+    const int L = xcd * q + min(xcd, rem) + l;
+    const int group = kGroupM * tiles_j;
+    const int g0 = (L / group) * kGroupM;
+    const int gm = min(kGroupM, tiles_i - g0);
+    const int within = L - (L / group) * group;
+    ti = g0 + within % gm;
+    tj = within / gm;
+  }
   const int ib0 = ti * 2, ib1 = min(ti * 2 + 1, p.nib - 1);
   const int jb0 = tj * 2, jb1 = min(tj * 2 + 1, p.njb - 1);
   const int jb = (jq >> 1) ? jb1 : jb0;   // the j-block this wave multiplies with
 
   // ---- what this wave stages: waves 0-3 the A pair, waves 4-7 the B pair, 8 KiB each
   const bool stage_a = w < 4;
-  const int sblk = (w & 2) ? (stage_a ? ib1 : jb1) : (stage_a ? ib0 : jb0);
   const int shalf = (w >> 1) & 1;            // which block of the pair
+  const int sblk = shalf ? (stage_a ? ib1 : jb1) : (stage_a ? ib0 : jb0);
   const int soff = shalf * kBlockBytes + (w & 1) * (kBlockBytes / 2);
   const int8_t* const smain = (stage_a ? p.a_codes : p.b_codes) +
                               (int64_t)sblk * p.nkb * kBlockBytes + (w & 1) * (kBlockBytes / 2);
 
   // Scales and slots are read-only for the whole kernel: reading them through the constant
-  // address space makes them scalar loads, which do not share a counter with the LDS loads.
+  // address space makes them scalar loads, which do not share a counter with the vector loads.
   typedef const __attribute__((address_space(4))) float cfloat;
   typedef const __attribute__((address_space(4))) int32_t cint;
   cfloat* const a_sc = (cfloat*)p.a_scales;
@@ -94,177 +219,263 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
   cint* const a_sl = (cint*)p.a_slot;
   const bool has_fb = p.a_slot != nullptr;
   const int ia0 = ib0 * p.a_si, ia1 = ib1 * p.a_si, ibj = jb * p.b_sj;
+  const int nkb = p.nkb;
 
-  float acc[4][2][16];
+  auto load_rec = [&](int k) -> KRec {
+    KRec r{-1, -1, 0.0f, 0.0f, 0.0f};
+    if (k < nkb) {
+      if (has_fb) {
+        r.slot0 = a_sl[ia0 + k * p.a_sk];
+        r.slot1 = a_sl[ia1 + k * p.a_sk];
+      }
+      r.sa0 = a_sc[ia0 + k * p.a_sk];
+      r.sa1 = a_sc[ia1 + k * p.a_sk];
+      r.sb = b_sc[ibj + k * p.b_sk];
+    }
+    return r;
+  };
+  // Stages this wave's 8 KiB share of item (k, res) into ring slot `asel` (A) / k & 1 (B).
+  auto stage_item = [&](int k, int res, const KRec& r, int asel, bool new_b) {
+    if (stage_a) {
+      const int8_t* src;
+      if (res) {
+        const int s = shalf ? r.slot1 : r.slot0;
+        if (s < 0) return;   // unflagged half: nothing to bring (its scale will be zero)
+        src = p.a_res + (int64_t)s * kBlockBytes + (w & 1) * (kBlockBytes / 2);
+      } else {
+        src = smain + (int64_t)k * kBlockBytes;
+      }
+      stage_half_block(src, a_ring + asel * kRingBytes + soff, lane);
+    } else if (new_b) {
+      stage_half_block(smain + (int64_t)k * kBlockBytes, b_ring + (k & 1) * kRingBytes + soff, lane);
+    }
+  };
+
+  WaveState st;
+  float (&acc)[4][2][16] = st.acc;
 #pragma unroll
   for (int si = 0; si < 4; ++si)
 #pragma unroll
     for (int sj = 0; sj < 2; ++sj)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[si][sj][r] = 0.0f;
+      for (int r = 0; r < 16; ++r) st.acc[si][sj][r] = 0.0f;
   bool poison0 = false, poison1 = false;
-
-  const int k_begin = kDebug ? p.debug_k : 0;
-  const int k_end = kDebug ? p.debug_k + 1 : p.nkb;
-  if (k_begin >= k_end) goto store;   // empty contraction: all zeros
+  if (nkb <= 0) goto store;   // empty contraction: all zeros
 
   {
-  // prologue: main item of the first k-block into ring slot 0
-  stage_half_block(smain + (int64_t)k_begin * kBlockBytes,
-                   (stage_a ? a_ring : b_ring) + soff, lane);
-
-  // scalars of the current k-block, fetched one item ahead
-  int slot0 = has_fb ? a_sl[ia0 + k_begin * p.a_sk] : -1;
-  int slot1 = has_fb ? a_sl[ia1 + k_begin * p.a_sk] : -1;
-  float sa0 = a_sc[ia0 + k_begin * p.a_sk], sa1 = a_sc[ia1 + k_begin * p.a_sk];
-  float sb = b_sc[ibj + k_begin * p.b_sk];
-  float rs0 = 0.0f, rs1 = 0.0f;
-
-  int k = k_begin;
-  int res = 0;     // 0: main item, 1: residual item of k
-  int t = 0;       // item counter: A ring slot = t & 1
-  while (k < k_end) {
-    // this wave's direct-to-LDS loads must have landed before the barrier publishes them
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    // ---- prologue: items 0 and 1 into the two ring slots
+    // records are fetched two k-blocks ahead so that no scalar load is waited for in the loop
+    KRec r0 = load_rec(0), r1 = load_rec(1), r2 = load_rec(2);
+    int k = 0, res = 0, t = 0;
+    stage_item(0, 0, r0, 0, true);
+    {
+      const bool n1res = r0.slot0 >= 0 || r0.slot1 >= 0;
+      if (n1res) stage_item(0, 1, r0, 1, false);
+      else if (1 < nkb) stage_item(1, 0, r1, 1, true);
+    }
+    float rs0 = 0.0f, rs1 = 0.0f;          // residual scales of the current k-block
+    if (r0.slot0 >= 0) rs0 = r_sc[r0.slot0];
+    if (r0.slot1 >= 0) rs1 = r_sc[r0.slot1];
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0): this wave's direct-to-LDS loads landed
     __syncthreads();
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      st.aq[g] = lds_frag(a_ring, 2 * h, g, lane);
+      st.bq[0][g] = lds_frag(b_ring + (jq >> 1) * kBlockBytes, 2 * (jq & 1), g, lane);
+      st.bq[1][g] = lds_frag(b_ring + (jq >> 1) * kBlockBytes, 2 * (jq & 1) + 1, g, lane);
+    }
+    st.P[1] = v16i{0};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) st.T[i] = 0.0f;
+    float sp = 0.0f;                       // scale of the previous item's second i-block
 
-    const int bsel = (k - k_begin) & 1;
-    const int asel = t & 1;
+    for (;;) {
+      // ---- the items after this one (all wave-uniform scalar logic)
+      const bool n1res = !res && (r0.slot0 >= 0 || r0.slot1 >= 0);
+      const int n1k = n1res ? k : k + 1;
+      const bool has1 = n1k < nkb;
+      const bool n2res = !n1res && (r1.slot0 >= 0 || r1.slot1 >= 0);
+      const int n2k = (n1res || n2res) ? k + 1 : k + 2;
+      const bool has2 = n2k < nkb;
 
-    // ---- prefetch the next item
-    const bool next_res = !res && (slot0 >= 0 || slot1 >= 0);
-    const int next_k = next_res ? k : k + 1;
-    if (next_res) {
-      if (stage_a) {
-        const int s = shalf ? slot1 : slot0;
-        if (s >= 0)
-          stage_half_block(p.a_res + (int64_t)s * kBlockBytes + (w & 1) * (kBlockBytes / 2),
-                           a_ring + (asel ^ 1) * kRingBytes + soff, lane);
+      // ---- scales of this item
+      float s0, s1;
+      if (!res) {
+        s0 = r0.sa0 * r0.sb;
+        s1 = r0.sa1 * r0.sb;
+        poison0 |= r0.slot0 == -2;
+        poison1 |= r0.slot1 == -2;
+      } else {   // an unflagged half multiplies stale LDS contents by zero: adds +0
+        s0 = r0.slot0 >= 0 ? rs0 * r0.sb : 0.0f;
+        s1 = r0.slot1 >= 0 ? rs1 * r0.sb : 0.0f;
       }
-      if (slot0 >= 0) rs0 = r_sc[slot0];
-      if (slot1 >= 0) rs1 = r_sc[slot1];
-    } else if (next_k < k_end) {
-      stage_half_block(smain + (int64_t)next_k * kBlockBytes,
-                       (stage_a ? a_ring + (asel ^ 1) * kRingBytes
-                                : b_ring + (bsel ^ 1) * kRingBytes) + soff, lane);
-    }
-    // scalars of k-block k+1 (used from the next main item on)
-    int nslot0 = -1, nslot1 = -1;
-    float nsa0 = 0.0f, nsa1 = 0.0f, nsb = 0.0f;
-    if (!next_res && next_k < k_end) {
-      if (has_fb) {
-        nslot0 = a_sl[ia0 + next_k * p.a_sk];
-        nslot1 = a_sl[ia1 + next_k * p.a_sk];
+
+      const int8_t* const a_cur = a_ring + (t & 1) * kRingBytes;
+      const int8_t* const a_nxt = a_ring + ((t + 1) & 1) * kRingBytes;
+      const int8_t* const b_nxt = b_ring + (n1k & 1) * kRingBytes + (jq >> 1) * kBlockBytes;
+
+      run_unit<0>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
+      run_unit<1>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
+      run_unit<2>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
+      run_unit<3>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
+      run_unit<4>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
+      run_unit<5>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
+
+      // All LDS reads of this item are issued (units 6, 7 run from registers).  Wait for them
+      // and for the next item's direct-to-LDS loads, then the barrier publishes the next item
+      // and frees this item's ring slots for the item after it.
+      __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+      __syncthreads();
+      if (has2) {
+        if (n2res) stage_item(k + 1, 1, r1, t & 1, false);
+        else stage_item(n2k, 0, r1, t & 1, n2k != n1k);
       }
-      nsa0 = a_sc[ia0 + next_k * p.a_sk];
-      nsa1 = a_sc[ia1 + next_k * p.a_sk];
-      nsb = b_sc[ibj + next_k * p.b_sk];
+
+      run_unit<6>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
+      run_unit<7>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
+
+      sp = s1;
+      if (!has1) break;
+      // ---- advance to the next item
+      ++t;
+      if (n1res) {
+        res = 1;
+      } else {
+        res = 0;
+        ++k;
+        r0 = r1;
+        r1 = r2;
+        r2 = load_rec(k + 2);
+        rs0 = rs1 = 0.0f;
+        if (r0.slot0 >= 0) rs0 = r_sc[r0.slot0];
+        if (r0.slot1 >= 0) rs1 = r_sc[r0.slot1];
+      }
     }
-
-    // ---- scales of this item (wave-uniform scalars)
-    float s0, s1;
-    bool do0 = true, do1 = true;
-    if (!res) {
-      s0 = sa0 * sb;
-      s1 = sa1 * sb;
-      poison0 |= slot0 == -2;
-      poison1 |= slot1 == -2;
-    } else {
-      do0 = slot0 >= 0;
-      do1 = slot1 >= 0;
-      s0 = rs0 * sb;
-      s1 = rs1 * sb;
-    }
-    const bool record = !kDebug || (res == p.debug_residual);
-
-    const int8_t* la = a_ring + asel * kRingBytes;
-    const int8_t* lb = b_ring + bsel * kRingBytes + (jq >> 1) * kBlockBytes;
-
-    v4i bq[2][4];
+    drain(st, sp);
+  }
+store:
+  // ---- epilogue.  The MFMA result layout (lane = column, registers = rows) would give 64-byte
+  // global stores; instead each wavefront transposes its tile through a private LDS patch
+  // (64 rows x 64 columns of FP32 at a time, row pitch 72 floats: conflict-free both ways) and
+  // writes whole 128/256-byte row segments with 16-byte stores.
+  __syncthreads();   // every wavefront is done reading the operand rings
+  if (tj * 2 + (jq >> 1) >= p.njb) return;
+  float* const stg = reinterpret_cast<float*>(lds + w * kStageBytesPerWave);
+  const int col0 = jb * kBlock + (jq & 1) * 64;        // first column of this wave's tile
 #pragma unroll
-    for (int sj = 0; sj < 2; ++sj)
+  for (int half = 0; half < 2; ++half) {
+    if (half && ti * 2 + 1 >= p.nib) break;
+    const bool poison = !kDebug && (half ? poison1 : poison0);
+    // a flagged block whose residual found no slot cannot be computed: poison its rows
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) bq[sj][ks] = lds_frag(lb, 2 * (jq & 1) + sj, ks, lane);
-
+    for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-    for (int si = 0; si < 4; ++si) {
-      const bool active = (si < 2) ? do0 : do1;
-      if (!active) continue;   // wave-uniform
-      const float s = (si < 2) ? s0 : s1;
-      const int8_t* lablk = la + (si >> 1) * kBlockBytes;
-      v4i aq[4];
+      for (int sj = 0; sj < 2; ++sj)
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) aq[ks] = lds_frag(lablk, 2 * h + (si & 1), ks, lane);
+        for (int r = 0; r < 16; ++r) {
+          const int rl = s2 * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          const int cl = sj * 32 + (lane & 31);
+          stg[rl * kStagePitch + cl] = poison ? __int_as_float(0x7FC00000) : acc[half * 2 + s2][sj][r];
+        }
+    const int row0 = (half ? ib1 : ib0) * kBlock + h * 64;
+    if (!kDebug && p.out_bf16) {
+      uint16_t* const C = reinterpret_cast<uint16_t*>(p.c);
+      const int c8 = (lane & 7) * 8;
 #pragma unroll
-      for (int sj = 0; sj < 2; ++sj) {
-        v16i P = {0};
+      for (int it = 0; it < 8; ++it) {
+        const int rl = it * 8 + (lane >> 3);
+        const int row = row0 + rl, col = col0 + c8;
+        const float4 lo = *reinterpret_cast<const float4*>(stg + rl * kStagePitch + c8);
+        const float4 hi = *reinterpret_cast<const float4*>(stg + rl * kStagePitch + c8 + 4);
+        if (row >= p.M || col >= p.N) continue;
+        uint16_t* dst = C + (int64_t)row * p.ldc + col;
+        if (p.vec_ok && col + 8 <= p.N) {
+          v4i o;
+          o[0] = pack_bf16x2(lo.x, lo.y); o[1] = pack_bf16x2(lo.z, lo.w);
+          o[2] = pack_bf16x2(hi.x, hi.y); o[3] = pack_bf16x2(hi.z, hi.w);
+          *reinterpret_cast<v4i*>(dst) = o;
+        } else {
+          const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-          P = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[ks], bq[sj][ks], P, 0, 0, 0);
-        if (record) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            if (kDebug) acc[si][sj][r] = __int_as_float(P[r]);
-            else acc[si][sj][r] = __builtin_fmaf((float)P[r], s, acc[si][sj][r]);
-          }
+          for (int e = 0; e < 8; ++e)
+            if (col + e < p.N) dst[e] = (uint16_t)float_to_bf16_bits(v[e]);
         }
       }
-    }
-
-    // ---- advance
-    if (next_res) {
-      res = 1;
     } else {
-      res = 0;
-      k = k + 1;
-      slot0 = nslot0; slot1 = nslot1; sa0 = nsa0; sa1 = nsa1; sb = nsb;
-    }
-    ++t;
-  }
-  }
-
-store:
-  // ---- store: sub-tile (si, sj), register r -> row 8*(r/4) + 4*(lane/32) + r%4, column lane%32
-  if (tj * 2 + (jq >> 1) >= p.njb) return;
-  const int col_base = jb * kBlock + (jq & 1) * 64 + (lane & 31);
+      float* const C = reinterpret_cast<float*>(p.c);
+      const int c4 = (lane & 15) * 4;
 #pragma unroll
-  for (int si = 0; si < 4; ++si) {
-    if ((si >> 1) && ti * 2 + 1 >= p.nib) continue;
-    const int ib = (si >> 1) ? ib1 : ib0;
-    const bool poison = !kDebug && ((si >> 1) ? poison1 : poison0);
-    const int row_base = ib * kBlock + h * 64 + (si & 1) * 32 + 4 * (lane >> 5);
+      for (int it = 0; it < 16; ++it) {
+        const int rl = it * 4 + (lane >> 4);
+        const int row = row0 + rl, col = col0 + c4;
+        const float4 v = *reinterpret_cast<const float4*>(stg + rl * kStagePitch + c4);
+        if (row >= p.M || col >= p.N) continue;
+        float* dst = C + (int64_t)row * p.ldc + col;
+        if (p.vec_ok && col + 4 <= p.N) {
+          *reinterpret_cast<float4*>(dst) = v;
+        } else {
+          const float e4[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-    for (int sj = 0; sj < 2; ++sj) {
-      const int col = col_base + sj * 32;
-      if (col >= p.N) continue;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = row_base + 8 * (r >> 2) + (r & 3);
-        if (row >= p.M) continue;
-        // a flagged block whose residual found no slot cannot be computed: poison its rows
-        const float v = poison ? __int_as_float(0x7FC00000) : acc[si][sj][r];
-        const int64_t off = (int64_t)row * p.ldc + col;
-        if (!kDebug && p.out_bf16)
-          reinterpret_cast<uint16_t*>(p.c)[off] = (uint16_t)float_to_bf16_bits(v);
-        else
-          reinterpret_cast<float*>(p.c)[off] = v;
+          for (int e = 0; e < 4; ++e)
+            if (col + e < p.N) dst[e] = e4[e];
+        }
       }
     }
   }
 }
 
+// The INT32 block product of one k-block, main or residual term (inspection / tests): one
+// workgroup per 128 x 128 output block, wavefront w computes rows [32w, 32w+32) straight from
+// global memory.
+__global__ __launch_bounds__(256) void partials_kernel(GemmParams p) {
+  const int ib = blockIdx.x / p.njb, jb = blockIdx.x - ib * p.njb;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int k = p.debug_k;
+  const int8_t* ablk = p.a_codes + ((int64_t)ib * p.nkb + k) * kBlockBytes;
+  bool zero = false;
+  if (p.debug_residual) {
+    const int slot = p.a_slot ? p.a_slot[ib * p.a_si + k * p.a_sk] : -1;
+    zero = slot < 0;
+    ablk = p.a_res + (int64_t)(zero ? 0 : slot) * kBlockBytes;
+  }
+  const int8_t* bblk = p.b_codes + ((int64_t)jb * p.nkb + k) * kBlockBytes;
+  int32_t* const out = reinterpret_cast<int32_t*>(p.c);
+#pragma unroll
+  for (int sj = 0; sj < 4; ++sj) {
+    v16i P = {0};
+    if (!zero) {
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const v4i a = *reinterpret_cast<const v4i*>(ablk + ((w * 4 + ks) * 64 + lane) * 16);
+        const v4i b = *reinterpret_cast<const v4i*>(bblk + ((sj * 4 + ks) * 64 + lane) * 16);
+        P = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, P, 0, 0, 0);
+      }
+    }
+    const int col = jb * kBlock + sj * 32 + (lane & 31);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = ib * kBlock + w * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      if (row < p.M && col < p.N) out[(int64_t)row * p.ldc + col] = P[r];
+    }
+  }
+}
+
 hipError_t launch_gemm(const GemmParams& p, bool debug, hipStream_t st) {
+  if (debug) {
+    if (p.nib * p.njb == 0) return hipSuccess;
+    hipLaunchKernelGGL(partials_kernel, dim3(p.nib * p.njb), dim3(256), 0, st, p);
+    return hipGetLastError();
+  }
   const int tiles = ((p.nib + 1) / 2) * ((p.njb + 1) / 2);
   if (tiles == 0) return hipSuccess;
-  static bool attr_set[2] = {false, false};
-  auto kern = debug ? gemm_kernel<true> : gemm_kernel<false>;
-  if (!attr_set[debug]) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
-    attr_set[debug] = true;
+    attr_set = true;
   }
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), kLdsBytes, st, p);
+  hipLaunchKernelGGL(gemm_kernel, dim3(tiles), dim3(kThreads), kLdsBytes, st, p);
   return hipGetLastError();
 }
 

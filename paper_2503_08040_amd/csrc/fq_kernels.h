@@ -45,6 +45,7 @@ struct GemmParams {
   int M, N;                   // valid output extent
   int nib, njb, nkb;
   int out_bf16;
+  int vec_ok;                 // C base and row pitch allow 16-byte stores
   int debug_k;                // debug mode: the single k-block to evaluate
   int debug_residual;         // debug mode: 0 main term, 1 residual term
 };
