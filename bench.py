@@ -22,6 +22,9 @@ sys.path.insert(0, ROOT)
 
 INT8_PEAK_TOPS = 5000.0     # MI355X dense INT8 MFMA peak (published), TOP/s
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes per fq_gemm launch from rocprofv3 FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00), both
+# scaled by what the same counters read for a 1 GiB copy (profiles/gemm_quantize_cfg2_hbm_traffic.md)
+MEASURED_GEMM_TRAFFIC_BYTES = {"cfg2_glu_upgate_4096x4096x11008": 300.3e6 + 90.2e6}
 
 
 def log(*a):
@@ -47,7 +50,7 @@ def make_workload(name):
 def cpu_baseline(wl, budget_s=15.0):
     """Times the CPU oracle (as it stands) on a bounded window of the same workload."""
     from oracle import fqo
-    rows = min(wl.M, 1024)
+    rows = min(wl.M, 4096)
     t0 = time.perf_counter()
     oa = fqo.quantize(wl.X[:rows], 128, fqo.CRIT_ABSMAX_GT, wl.theta)
     tq = time.perf_counter() - t0
@@ -83,6 +86,9 @@ def main():
                     help="minimum duration of the untimed warm-up (clock ramp)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of 1 GiB (5 times) and exit: gives the "
+                         "profiler's FETCH_SIZE / WRITE_SIZE counters a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures one GPU: this build has no multi-GPU path "
@@ -93,6 +99,15 @@ def main():
 
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4,
+                          "calibrate_copy_bytes_written": src.numel() * 4}), flush=True)
+        return
     log(f"[bench] generating {args.workload}")
     wl = make_workload(args.workload)
     M, K, N = wl.M, wl.K, wl.N
@@ -156,9 +171,11 @@ def main():
         "ms_quantize": round(ms_quant, 5), "ms_gemm": round(ms_gemm, 5),
         "gemm_only_tops": round(ops / (ms_gemm * 1e-3) / 1e12, 2),
         "quantizer_gbs": round(quant_bytes / (ms_quant * 1e-3) / 1e9, 1),
-        "roofline": {"bound": "mfma", "kernel": "fq::gemm_kernel<false>",
+        "roofline": {"bound": "mfma", "kernel": "fq::gemm_kernel",
                      "achieved": round(achieved, 2), "peak": INT8_PEAK_TOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / INT8_PEAK_TOPS, 4), "traffic": None,
+                     "frac": round(achieved / INT8_PEAK_TOPS, 4),
+                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(wl.name)
+                     if args.out_dtype == "bf16" else None,
                      "note": "INT8 ops: 2*M*N*K*(1+f) per launch / HIP-event time of fq_gemm"},
     }
 
