@@ -16,7 +16,9 @@
  *   - Every data pointer is caller-owned DEVICE memory (hipMalloc'ed or a
  *     PyTorch CUDA/HIP tensor's storage) unless a comment says "host".  The
  *     library never allocates, frees or retains device memory and keeps no
- *     state between calls.  fq_qtensor structs themselves live in host memory.
+ *     hidden state: all that is carried from one call to the next lives in the
+ *     caller's fq_qtensor (its `epoch` field and `fb_counters` buffer).
+ *     fq_qtensor structs themselves live in host memory.
  *   - Calls enqueue kernels on `hip_stream` (a hipStream_t passed as void*;
  *     NULL is the default stream) and return without waiting.
  *   - Arguments are validated on the host before anything is launched; a
@@ -89,14 +91,21 @@ typedef struct {
   int32_t block;         /* 128                                                  */
   int32_t capacity;      /* number of residual slots the res_* buffers hold      */
   int32_t criterion;     /* host: fq_criterion of the last fq_quantize into this */
-  int32_t reserved;
+  int32_t epoch;         /* host: fq_quantize calls made into this tensor (library-managed;
+                            fq_qtensor_bind sets 0; selects the live counter)         */
   int8_t *codes;         /* [nbr*nbc][16384] tile order, Q^(G)        (Sec. 3.1) */
   int8_t *codes_t;       /* [nbc*nbr][16384] tile order of G^T, or NULL          */
   float *scales;         /* [nbr, nbc]  a_{i,k} = max|G_ik| / 127     (Sec. 3.1) */
   uint8_t *mask;         /* [nbr, nbc]  u(i,k)                        (Sec. 4.4) */
-  int32_t *fb_count;     /* [1]  number of flagged blocks (may exceed capacity)  */
-  int32_t *fb_list;      /* [nbr*nbc] ascending ids bi*nbc+bk of flagged blocks;
-                            entries past fb_count are -1                         */
+  int32_t *fb_count;     /* [1]  number of flagged blocks (may exceed capacity).
+                            Points at one of the two fb_counters; fq_quantize
+                            re-points it on every call                           */
+  int32_t *fb_counters;  /* [2]  the two alternating slot counters: a call counts
+                            in one and clears the other for the next call, so the
+                            quantizer is a single kernel launch                  */
+  int32_t *fb_list;      /* [capacity] compact list of flagged blocks in slot order:
+                            fb_list[s] = bi*nbc+bk of the block in slot s, for
+                            s < min(fb_count, capacity); the rest is unspecified */
   int32_t *fb_slot;      /* [nbr, nbc] residual slot of the block, -1 if not
                             flagged, -2 if flagged but no slot was left. Slots
                             are a bijection onto [0, fb_count) in no fixed order */
@@ -126,6 +135,7 @@ fq_status fq_qtensor_bind(void *base, int32_t rows, int32_t cols, int32_t block,
  *   division correctly rounded.  Non-finite inputs give unspecified codes.
  * Outputs: every buffer of `out` that is not NULL-optional (codes, scales,
  * mask, fb_count, fb_list, fb_slot; res_* when capacity > 0; *_t when set).
+ * The first call into a freshly bound tensor also clears fb_counters.
  * out->capacity may be 0 only with FQ_CRIT_NONE.  If more blocks are flagged
  * than there are slots, the surplus blocks get fb_slot = -2, fb_count still
  * reports the true count, and any fq_gemm using the tensor as A writes NaN to

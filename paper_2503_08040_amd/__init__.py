@@ -28,9 +28,10 @@ EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_gemm",
 class fq_qtensor(C.Structure):
     """Mirror of the C struct fq_qtensor."""
     _fields_ = [("rows", C.c_int32), ("cols", C.c_int32), ("block", C.c_int32),
-                ("capacity", C.c_int32), ("criterion", C.c_int32), ("reserved", C.c_int32),
+                ("capacity", C.c_int32), ("criterion", C.c_int32), ("epoch", C.c_int32),
                 ("codes", C.c_void_p), ("codes_t", C.c_void_p), ("scales", C.c_void_p),
-                ("mask", C.c_void_p), ("fb_count", C.c_void_p), ("fb_list", C.c_void_p),
+                ("mask", C.c_void_p), ("fb_count", C.c_void_p), ("fb_counters", C.c_void_p),
+                ("fb_list", C.c_void_p),
                 ("fb_slot", C.c_void_p), ("res_codes", C.c_void_p), ("res_codes_t", C.c_void_p),
                 ("res_scales", C.c_void_p)]
 
@@ -130,7 +131,7 @@ class QTensor:
             "scales": (torch.float32, (self.nbr, self.nbc), 4),
             "mask": (torch.uint8, (self.nbr, self.nbc), 1),
             "fb_count": (torch.int32, (1,), 4),
-            "fb_list": (torch.int32, (nb,), 4),
+            "fb_list": (torch.int32, (self.capacity,), 4),
             "fb_slot": (torch.int32, (self.nbr, self.nbc), 4),
             "res_codes": (torch.int8, (self.capacity, FQ_BLOCK_BYTES), 1),
             "res_codes_t": (torch.int8, (self.capacity, FQ_BLOCK_BYTES), 1),

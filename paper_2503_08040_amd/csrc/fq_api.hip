@@ -13,7 +13,7 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct Layout {
-  size_t codes, codes_t, scales, mask, fb_count, fb_list, fb_slot, res_codes, res_codes_t,
+  size_t codes, codes_t, scales, mask, fb_counters, fb_list, fb_slot, res_codes, res_codes_t,
       res_scales, total;
 };
 
@@ -28,8 +28,8 @@ bool compute_layout(int32_t rows, int32_t cols, int32_t block, int32_t capacity,
   L->codes_t = want_t ? take((size_t)nb * FQ_BLOCK_BYTES) : (size_t)-1;
   L->scales = take((size_t)nb * 4);
   L->mask = take((size_t)nb);
-  L->fb_count = take(4);
-  L->fb_list = take((size_t)nb * 4);
+  L->fb_counters = take(8);
+  L->fb_list = take((size_t)capacity * 4);
   L->fb_slot = take((size_t)nb * 4);
   L->res_codes = take((size_t)capacity * FQ_BLOCK_BYTES);
   L->res_codes_t = want_t ? take((size_t)capacity * FQ_BLOCK_BYTES) : (size_t)-1;
@@ -42,9 +42,9 @@ fq_status check_qtensor(const fq_qtensor* t) {
   if (!t) return FQ_ERR_NULL;
   if (t->block != FQ_BLOCK) return FQ_ERR_BLOCK;
   if (t->rows < 0 || t->cols < 0 || t->capacity < 0) return FQ_ERR_SHAPE;
-  if (!t->codes || !t->scales || !t->mask || !t->fb_count || !t->fb_list || !t->fb_slot)
+  if (!t->codes || !t->scales || !t->mask || !t->fb_count || !t->fb_counters || !t->fb_slot)
     return FQ_ERR_NULL;
-  if (t->capacity > 0 && (!t->res_codes || !t->res_scales)) return FQ_ERR_NULL;
+  if (t->capacity > 0 && (!t->res_codes || !t->res_scales || !t->fb_list)) return FQ_ERR_NULL;
   if (t->capacity > 0 && t->codes_t && !t->res_codes_t) return FQ_ERR_NULL;
   return FQ_OK;
 }
@@ -118,12 +118,13 @@ fq_status fq_qtensor_bind(void* base, int32_t rows, int32_t cols, int32_t block,
   if ((uintptr_t)base & 255) return FQ_ERR_SHAPE;
   char* b = static_cast<char*>(base);
   out->rows = rows; out->cols = cols; out->block = block; out->capacity = capacity;
-  out->criterion = FQ_CRIT_NONE; out->reserved = 0;
+  out->criterion = FQ_CRIT_NONE; out->epoch = 0;
   out->codes = reinterpret_cast<int8_t*>(b + L.codes);
   out->codes_t = want_transposed ? reinterpret_cast<int8_t*>(b + L.codes_t) : nullptr;
   out->scales = reinterpret_cast<float*>(b + L.scales);
   out->mask = reinterpret_cast<uint8_t*>(b + L.mask);
-  out->fb_count = reinterpret_cast<int32_t*>(b + L.fb_count);
+  out->fb_counters = reinterpret_cast<int32_t*>(b + L.fb_counters);
+  out->fb_count = out->fb_counters;
   out->fb_list = reinterpret_cast<int32_t*>(b + L.fb_list);
   out->fb_slot = reinterpret_cast<int32_t*>(b + L.fb_slot);
   out->res_codes = reinterpret_cast<int8_t*>(b + L.res_codes);
@@ -154,7 +155,15 @@ fq_status fq_quantize(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld
   p.crit = (int)crit; p.theta = theta; p.capacity = out->capacity;
   p.codes = out->codes; p.codes_t = out->codes_t;
   p.scales = out->scales; p.mask = out->mask;
-  p.fb_count = out->fb_count; p.fb_list = out->fb_list; p.fb_slot = out->fb_slot;
+  // Two alternating counters: this call counts in one and clears the other for the next call.
+  const bool first = out->epoch == 0;
+  const int live = out->epoch & 1;
+  p.fb_count = out->fb_counters + live;
+  p.fb_count_next = out->fb_counters + (live ^ 1);
+  p.clear_both = (first || empty) ? 1 : 0;
+  out->fb_count = empty ? out->fb_counters : p.fb_count;
+  out->epoch = empty ? 2 : (out->epoch >= (1 << 30) ? 2 + (live ^ 1) : out->epoch + 1);
+  p.fb_list = out->fb_list; p.fb_slot = out->fb_slot;
   p.res_codes = out->res_codes; p.res_codes_t = out->res_codes_t; p.res_scales = out->res_scales;
   out->criterion = (int32_t)crit;
   if (fq::launch_quantize(p, static_cast<hipStream_t>(hip_stream)) != hipSuccess)

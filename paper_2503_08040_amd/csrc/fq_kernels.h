@@ -18,7 +18,9 @@ struct QuantParams {
   int8_t* codes_t;     // nullptr: no transposed copies
   float* scales;
   uint8_t* mask;
-  int32_t* fb_count;
+  int32_t* fb_count;       // live slot counter of this call (zero on entry)
+  int32_t* fb_count_next;  // counter of the next call: cleared by this call
+  int clear_both;          // first use of the tensor (or empty input): clear both counters first
   int32_t* fb_list;
   int32_t* fb_slot;
   int8_t* res_codes;

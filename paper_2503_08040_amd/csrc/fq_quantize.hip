@@ -1,5 +1,6 @@
 // Fused block quantizer: abs-max, INT8 codes, fallback decision, residual
-// quantization and slot allocation in one pass over the bf16 input.
+// quantization, slot allocation and the compact list of flagged blocks in one
+// kernel launch, one pass over the bf16 input.
 //
 // Paper: Sec. 3.1 (a = max|G|/127, Q^ = round(G/a)), Sec. 4.4
 // (u = [max|G| > theta]), Sec. 4.3 (second step on the residual G - a Q^),
@@ -153,6 +154,8 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
     p.scales[blk] = a;
     p.mask[blk] = u ? 1 : 0;
     p.fb_slot[blk] = slot;
+    if (slot >= 0) p.fb_list[slot] = blk;
+    if (blk == 0) *p.fb_count_next = 0;   // ready for the next call into this tensor
   }
   if (slot < 0) return;  // uniform over the workgroup
 
@@ -180,43 +183,12 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
   if (t == 0) p.res_scales[slot] = ra;
 }
 
-// fb_count = 0 before the quantizer allocates slots with it.
-__global__ void zero_count_kernel(int32_t* fb_count) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) *fb_count = 0;
-}
-
-// Ascending list of flagged block ids from the mask (one workgroup, any size).
-__global__ __launch_bounds__(1024) void fb_list_kernel(const uint8_t* mask, int n, int32_t* list) {
-  __shared__ int wsum[16];
-  __shared__ int base_sh;
-  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
-  if (t == 0) base_sh = 0;
-  __syncthreads();
-  for (int start = 0; start < n; start += 1024) {
-    const int i = start + t;
-    const int f = (i < n && mask[i]) ? 1 : 0;
-    // inclusive scan inside the wave
-    int s = f;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      int v = __shfl_up(s, off, 64);
-      if (lane >= off) s += v;
-    }
-    if (lane == 63) wsum[w] = s;
-    __syncthreads();
-    int before = base_sh;
-    for (int j = 0; j < w; ++j) before += wsum[j];
-    if (f) list[before + s - 1] = i;
-    __syncthreads();
-    if (t == 0) {
-      int tot = 0;
-      for (int j = 0; j < 16; ++j) tot += wsum[j];
-      base_sh += tot;
-    }
-    __syncthreads();
+// Clears both slot counters: first use of a tensor, or an empty input.
+__global__ void clear_counters_kernel(int32_t* live, int32_t* next) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    *live = 0;
+    *next = 0;
   }
-  const int total = base_sh;
-  for (int i = total + t; i < n; i += 1024) list[i] = -1;
 }
 
 // Tile order -> dense row-major (inspection / tests).
@@ -229,14 +201,14 @@ __global__ void untile_kernel(const int8_t* tiled, int rows, int cols, int nbc, 
 }
 
 hipError_t launch_quantize(const QuantParams& p, hipStream_t st) {
-  hipLaunchKernelGGL(zero_count_kernel, dim3(1), dim3(64), 0, st, p.fb_count);
+  if (p.clear_both)
+    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, st, p.fb_count, p.fb_count_next);
   const int nb = p.nbr * p.nbc;
   if (nb > 0) {
     if (p.codes_t)
       hipLaunchKernelGGL(quantize_kernel<true>, dim3(nb), dim3(kThreads), 0, st, p);
     else
       hipLaunchKernelGGL(quantize_kernel<false>, dim3(nb), dim3(kThreads), 0, st, p);
-    hipLaunchKernelGGL(fb_list_kernel, dim3(1), dim3(1024), 0, st, p.mask, nb, p.fb_list);
   }
   return hipGetLastError();
 }

@@ -58,10 +58,15 @@ def compare_quantized(gq: fq.QTensor, oq: fqo.QTensor, label=""):
     assert np.array_equal(gq.view("mask").cpu().numpy(), oq.mask), f"{label}: mask differs"
     n = int(gq.view("fb_count").cpu().numpy()[0])
     assert n == int(oq.fb_count[0]), f"{label}: fb_count {n} != {int(oq.fb_count[0])}"
-    lst = gq.view("fb_list").cpu().numpy()
-    assert np.array_equal(lst[:n], oq.fb_list[:n]), f"{label}: fb_list differs"
-    assert np.all(lst[n:] == -1), f"{label}: fb_list tail is not -1"
     slot = gq.view("fb_slot").cpu().numpy()
+    if gq.capacity > 0:
+        # compact list in slot order: the same set as the oracle's ascending list, and the
+        # inverse of the slot map
+        lst = gq.view("fb_list").cpu().numpy()[:min(n, gq.capacity)]
+        if n <= gq.capacity:
+            assert np.array_equal(np.sort(lst), oq.fb_list[:n]), f"{label}: fb_list differs"
+        assert np.array_equal(slot.ravel()[lst], np.arange(len(lst))), f"{label}: fb_list/fb_slot"
+
     flagged = oq.mask.astype(bool)
     assert np.all(slot[~flagged] == -1), f"{label}: unflagged block has a slot"
     if n <= gq.capacity:

@@ -40,9 +40,10 @@ def test_qtensor_bytes_and_bind():
     base = 0x10000
     assert fq.lib().fq_qtensor_bind(C.c_void_p(base), 130, 200, 128, 3, 1, C.byref(t)) == fq.FQ_OK
     assert (t.rows, t.cols, t.block, t.capacity) == (130, 200, 128, 3)
-    ptrs = [t.codes, t.codes_t, t.scales, t.mask, t.fb_count, t.fb_list, t.fb_slot, t.res_codes,
+    ptrs = [t.codes, t.codes_t, t.scales, t.mask, t.fb_counters, t.fb_list, t.fb_slot, t.res_codes,
             t.res_codes_t, t.res_scales]
     assert all(p and p % 256 == 0 for p in ptrs) and len(set(ptrs)) == len(ptrs)
+    assert t.fb_count == t.fb_counters and t.epoch == 0
     assert max(ptrs) < base + fq.fq_qtensor_bytes(130, 200, 3, True)
     assert fq.lib().fq_qtensor_bind(C.c_void_p(base + 8), 130, 200, 128, 3, 1, C.byref(t)) == fq.FQ_ERR_SHAPE
     assert fq.lib().fq_qtensor_bind(None, 130, 200, 128, 3, 1, C.byref(t)) == fq.FQ_ERR_NULL
