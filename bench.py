@@ -74,6 +74,71 @@ def cpu_baseline(wl, budget_s=15.0):
                       f"window (K={wl.K}); {tg:.2f}s gemm + {tq_share:.3f}s quantize share"}
 
 
+def _time_loop(fn, seconds, iters):
+    """Median-free simple timing: warm up for `seconds`, then time `iters` calls with events."""
+    import torch
+    t_w = time.perf_counter()
+    while time.perf_counter() - t_w < seconds:
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def sweep(args):
+    """BASELINE config 5: M = K = N = 8192, fallback fraction and placement swept."""
+    import torch
+    import paper_2503_08040_amd as fq
+    from paper_2503_08040_amd import synth
+    M = K = N = 8192
+    ops = 2.0 * M * N * K
+    rows = []
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    qx = fq.QTensor(M, K)
+    qw = fq.QTensor(N, K, capacity=0)
+    ms_bf16 = None
+    for placement in ("random", "sequential"):
+        for frac in (0.0, 0.01, 0.05, 0.2, 0.5, 1.0):
+            if placement == "sequential" and frac in (0.0, 1.0):
+                continue          # identical to the random placement
+            log(f"[sweep] f={frac} {placement}")
+            wl = synth.config5(frac=frac, placement=placement)
+            x = torch.from_numpy(wl.X.view(np.int16)).cuda().view(torch.bfloat16)
+            w = torch.from_numpy(wl.W.view(np.int16)).cuda().view(torch.bfloat16)
+            fq.fq_quantize(w, fq.FQ_CRIT_NONE, 0.0, out=qw)
+            fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, wl.theta, out=qx)
+            n_fb = fq.fq_qtensor_check(qx)
+            ms_q = _time_loop(lambda: fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, wl.theta, out=qx), 0.3, 50)
+            ms_g = _time_loop(lambda: fq.fq_gemm(fq.FQ_OP_NT, qx, qw, out=y), 1.0, 50)
+            if ms_bf16 is None:
+                ms_bf16 = _time_loop(lambda: torch.matmul(x, w.t(), out=y), 1.0, 50)
+            rows.append({"placement": placement, "f_target": frac, "f": n_fb / 4096.0,
+                         "ms_quantize": round(ms_q, 4), "ms_gemm": round(ms_g, 4),
+                         "tops_gemm": round(ops / ms_g / 1e9, 1),
+                         "tops_quant_plus_gemm": round(ops / (ms_q + ms_g) / 1e9, 1)})
+            del x, w
+    t0 = next(r for r in rows if r["f_target"] == 0.0)
+    for r in rows:
+        r["gemm_overhead_vs_f0"] = round(r["ms_gemm"] / t0["ms_gemm"], 3)
+        r["speedup_vs_bf16"] = round(ms_bf16 / (r["ms_quantize"] + r["ms_gemm"]), 3)
+    # crossover: first fraction (random placement) at which quantize+gemm is slower than bf16
+    rnd = [r for r in rows if r["placement"] == "random"]
+    cross = None
+    for a, b in zip(rnd, rnd[1:]):
+        ta, tb = a["ms_quantize"] + a["ms_gemm"], b["ms_quantize"] + b["ms_gemm"]
+        if ta <= ms_bf16 < tb:
+            cross = a["f"] + (b["f"] - a["f"]) * (ms_bf16 - ta) / (tb - ta)
+    return {"workload": "cfg5_square_8192", "bf16_gemm_ms": round(ms_bf16, 4),
+            "bf16_tflops": round(ops / ms_bf16 / 1e9, 1), "rows": rows,
+            "crossover_fraction_random": None if cross is None else round(cross, 3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -86,6 +151,9 @@ def main():
                     help="minimum duration of the untimed warm-up (clock ramp)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="config-5 sweep (8192^3): fallback fraction x placement, overhead curve and "
+                         "crossover against the bf16 GEMM; prints one JSON object with a table")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB (5 times) and exit: gives the "
                          "profiler's FETCH_SIZE / WRITE_SIZE counters a kernel of known traffic")
@@ -107,6 +175,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes_read": src.numel() * 4,
                           "calibrate_copy_bytes_written": src.numel() * 4}), flush=True)
+        return
+    if args.sweep:
+        print(json.dumps(sweep(args)), flush=True)
         return
     log(f"[bench] generating {args.workload}")
     wl = make_workload(args.workload)

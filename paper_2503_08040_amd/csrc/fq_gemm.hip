@@ -39,7 +39,7 @@ namespace {
 
 constexpr int kThreads = 512;
 constexpr int kXcds = 8;      // accelerator complex dies, each with a private L2
-constexpr int kGroupM = 4;    // tile rows per rasterization group
+constexpr int kGroupN = 4;    // tile columns per rasterization group
 constexpr int kRingBytes = 2 * kBlockBytes;     // one A pair or one B pair
 constexpr int kStagePitch = 72;                 // floats per row of the epilogue staging patch
 constexpr int kStageBytesPerWave = 64 * kStagePitch * 4;
@@ -184,6 +184,7 @@ __device__ __forceinline__ void drain(WaveState& st, float s1) {
 struct KRec {
   int slot0, slot1;
   float sa0, sa1, sb;
+  float rs0, rs1;   // residual scales of the two A blocks (valid where the slot is >= 0)
 };
 
 }  // namespace
@@ -201,8 +202,10 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
   // ---- tile of this workgroup; out-of-range blocks repeat the last valid one (never stored).
   // Workgroups are dealt to the 8 XCDs round-robin by id, and each XCD has its own L2.  Remap
   // ids so that one XCD works through a contiguous run of tiles, and order the tiles in groups
-  // of kGroupM tile-rows walked column by column: the ~32 tiles resident on an XCD then form a
-  // 4 x 8 patch that shares its A and B blocks through that L2.
+  // of kGroupN tile-columns walked row by row: the ~32 tiles resident on an XCD then form an
+  // 8 x 4 patch that shares its A and B blocks through that L2.  Grouping by columns (not rows)
+  // gives every XCD tiles from all tile-rows, so fallback blocks clustered in a few block-rows
+  // (the worst case of Sec. 6.3) load the XCDs evenly.
   const int tiles_i = (p.nib + 1) >> 1, tiles_j = (p.njb + 1) >> 1;
   int ti, tj;
   {
@@ -210,12 +213,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
     const int b = blockIdx.x, xcd = b % kXcds, l = b / kXcds;
     const int q = total / kXcds, rem = total % kXcds;
     const int L = xcd * q + min(xcd, rem) + l;
-    const int group = kGroupM * tiles_j;
-    const int g0 = (L / group) * kGroupM;
-    const int gm = min(kGroupM, tiles_i - g0);
+    const int group = kGroupN * tiles_i;
+    const int g0 = (L / group) * kGroupN;
+    const int gn = min(kGroupN, tiles_j - g0);
     const int within = L - (L / group) * group;
-    ti = g0 + within % gm;
-    tj = within / gm;
+    tj = g0 + within % gn;
+    ti = within / gn;
   }
   const int ib0 = ti * 2, ib1 = min(ti * 2 + 1, p.nib - 1);
   const int jb0 = tj * 2, jb1 = min(tj * 2 + 1, p.njb - 1);
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
   const int nkb = p.nkb;
 
   auto load_rec = [&](int k) -> KRec {
-    KRec r{-1, -1, 0.0f, 0.0f, 0.0f};
+    KRec r{-1, -1, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     if (k < nkb) {
       if (has_fb) {
         r.slot0 = a_sl[ia0 + k * p.a_sk];
@@ -253,6 +256,12 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
       r.sb = b_sc[ibj + k * p.b_sk];
     }
     return r;
+  };
+  // Residual scales depend on the slots, so they are fetched one step after the record itself:
+  // by then the slots have arrived and the dependent load does not stall the wavefront.
+  auto load_res_scales = [&](KRec& r) {
+    if (r.slot0 >= 0) r.rs0 = r_sc[r.slot0];
+    if (r.slot1 >= 0) r.rs1 = r_sc[r.slot1];
   };
   // Stages this wave's 8 KiB share of item (k, res) into ring slot `asel` (A) / k & 1 (B).
   auto stage_item = [&](int k, int res, const KRec& r, int asel, bool new_b) {
@@ -293,9 +302,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
       if (n1res) stage_item(0, 1, r0, 1, false);
       else if (1 < nkb) stage_item(1, 0, r1, 1, true);
     }
-    float rs0 = 0.0f, rs1 = 0.0f;          // residual scales of the current k-block
-    if (r0.slot0 >= 0) rs0 = r_sc[r0.slot0];
-    if (r0.slot1 >= 0) rs1 = r_sc[r0.slot1];
+    load_res_scales(r0);
+    load_res_scales(r1);
     __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0): this wave's direct-to-LDS loads landed
     __syncthreads();
 #pragma unroll
@@ -331,8 +339,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
         poison0 |= r0.slot0 == -2;
         poison1 |= r0.slot1 == -2;
       } else {   // an unflagged half multiplies stale LDS contents by zero: adds +0
-        s0 = r0.slot0 >= 0 ? rs0 * r0.sb : 0.0f;
-        s1 = r0.slot1 >= 0 ? rs1 * r0.sb : 0.0f;
+        s0 = r0.slot0 >= 0 ? r0.rs0 * r0.sb : 0.0f;
+        s1 = r0.slot1 >= 0 ? r0.rs1 * r0.sb : 0.0f;
       }
 
       const int8_t* const a_cur = a_ring + (t & 1) * kRingBytes;
@@ -370,10 +378,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
         ++k;
         r0 = r1;
         r1 = r2;
+        load_res_scales(r1);      // its slots were fetched an item ago
         r2 = load_rec(k + 2);
-        rs0 = rs1 = 0.0f;
-        if (r0.slot0 >= 0) rs0 = r_sc[r0.slot0];
-        if (r0.slot1 >= 0) rs1 = r_sc[r0.slot1];
       }
     }
     drain(st, sp);
