@@ -154,6 +154,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="config-5 sweep (8192^3): fallback fraction x placement, overhead curve and "
                          "crossover against the bf16 GEMM; prints one JSON object with a table")
+    ap.add_argument("--no-mfma-ceiling", action="store_true",
+                    help="skip the register-only MFMA throughput probe (about 3 s)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB (5 times) and exit: gives the "
                          "profiler's FETCH_SIZE / WRITE_SIZE counters a kernel of known traffic")
@@ -280,6 +282,16 @@ def main():
                                "tflops": round(ops / (ms_bf16 * 1e-3) / 1e12, 2),
                                "speedup_of_fq": round(ms_bf16 / ms_step, 3)}
 
+    if not args.no_mfma_ceiling:
+        # what the INT8 matrix cores sustain with no memory traffic (power-limited; context for
+        # roofline.frac, which stays relative to the published 5.0 POP/s)
+        import subprocess
+        tool = os.path.join(ROOT, "paper_2503_08040_amd", "mfma_ceiling")
+        if os.path.exists(tool):
+            torch.cuda.synchronize()
+            r = subprocess.run([tool], capture_output=True, text=True, timeout=120)
+            if r.returncode == 0:
+                result["mfma_ceiling"] = json.loads(r.stdout.strip().splitlines()[-1])
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample")
         result["cpu_baseline"] = cpu_baseline(wl)

@@ -15,6 +15,22 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Wall", "-Wno-unused-command-line-argument"]
 
 
+TOOL_SRC = os.path.join(CSRC, "tools", "mfma_ceiling.hip")
+TOOL_BIN = os.path.join(HERE, "mfma_ceiling")
+
+
+def build_tools() -> str:
+    """The register-only MFMA throughput probe used for the benchmark's roofline context."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature",
+           "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-o", TOOL_BIN,
+           TOOL_SRC]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed:\n{r.stderr}")
+    return TOOL_BIN
+
+
 def stale() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -41,3 +57,4 @@ def build(force: bool = True, extra_flags=()) -> str:
 
 if __name__ == "__main__":
     print(build())
+    print(build_tools())
