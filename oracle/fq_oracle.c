@@ -275,6 +275,102 @@ int fqo_gemm_partials(int op, const fqo_operand *A, const fqo_operand *B, int g,
   return 0;
 }
 
+/* ------------------------------------------------------------------------
+ * Stochastic rounding (Sec. 3.1: round x up to ceil(x) with probability
+ * x - floor(x), down otherwise; E[Q_s(x)] = x) for the tensors the paper
+ * quantizes that way: the output gradient dY and the stored activation
+ * context X (Sec. 5.1, Sec. 5.3), both plain block INT8 without fallback.
+ *
+ * The paper does not say where the random numbers come from.  Reading used
+ * here: element (r, c) of the matrix draws one 32-bit word from the
+ * counter-based generator Philox4x32-10 (Salmon, Moraes, Dror, Shaw, "Parallel
+ * random numbers: as easy as 1, 2, 3", SC'11) with key = the 64-bit seed and
+ * counter = (e >> 2) for e = r*cols + c, taking output word e & 3; its top 24
+ * bits u are compared with the fraction:  q = floor(t) + [u < (t-floor(t))*2^24],
+ * t = x/a in binary32 (all operations exact or single IEEE operations).
+ * Parity unpinned for non-finite inputs, as for round-to-nearest.
+ * ------------------------------------------------------------------------ */
+static void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                          uint32_t k0, uint32_t k1, uint32_t out[4]) {
+  for (int round = 0; round < 10; ++round) {
+    uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    uint32_t n1 = (uint32_t)p1;
+    uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    uint32_t n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Exposed so that the generator itself can be pinned to published test vectors. */
+void fqo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  philox4x32_10(ctr[0], ctr[1], ctr[2], ctr[3], key[0], key[1], out);
+}
+
+static uint32_t sr_word(uint64_t seed, uint64_t e) {
+  uint32_t o[4];
+  uint64_t ctr = e >> 2;
+  philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), 0u, 0u, (uint32_t)seed,
+                (uint32_t)(seed >> 32), o);
+  return o[e & 3];
+}
+
+int fqo_quantize_sr(const uint16_t *x_bf16, int rows, int cols, long ld, int g,
+                    uint64_t seed, int8_t *codes, float *scales) {
+  if (!x_bf16 || !codes || !scales) return -1;
+  if (rows < 0 || cols < 0 || g < 1 || ld < cols) return -2;
+  int nbr = (rows + g - 1) / g, nbc = (cols + g - 1) / g;
+  for (int bi = 0; bi < nbr; ++bi)
+    for (int bk = 0; bk < nbc; ++bk) {
+      int r0 = bi * g, r1 = r0 + g < rows ? r0 + g : rows;
+      int c0 = bk * g, c1 = c0 + g < cols ? c0 + g : cols;
+      float amax = 0.0f;
+      for (int r = r0; r < r1; ++r)
+        for (int c = c0; c < c1; ++c) {
+          float v = fabsf(bf16_to_f32(x_bf16[(size_t)r * ld + c]));
+          if (v > amax) amax = v;
+        }
+      float a = amax / 127.0f;
+      scales[bi * nbc + bk] = a;
+      for (int r = r0; r < r1; ++r)
+        for (int c = c0; c < c1; ++c) {
+          int8_t q = 0;
+          if (a != 0.0f) {
+            float t = bf16_to_f32(x_bf16[(size_t)r * ld + c]) / a;
+            float lo = floorf(t);
+            float frac = t - lo;                       /* exact */
+            uint32_t u = sr_word(seed, (uint64_t)r * (uint64_t)cols + (uint64_t)c) >> 8;
+            float v = lo + (((float)u < frac * 16777216.0f) ? 1.0f : 0.0f);
+            if (v > 127.0f) v = 127.0f;
+            if (v < -127.0f) v = -127.0f;
+            q = (int8_t)v;
+          }
+          codes[(size_t)r * cols + c] = q;
+        }
+    }
+  return 0;
+}
+
+/* ------------------------------------------------------------------------
+ * Delay Threshold (App. D, Alg. 2): after a training step, a layer's threshold
+ * is divided by alpha if its fallback rate was below r_min, multiplied by alpha
+ * if it was above r_max, left alone otherwise.  theta starts at 1.
+ * ------------------------------------------------------------------------ */
+float fqo_threshold_update(float theta, int n_fallback, int n_blocks, float r_min,
+                           float r_max, float alpha) {
+  if (n_blocks <= 0) return theta;
+  /* the rate is formed in binary32 like the bounds it is compared with, so that a rate of
+   * exactly r_min or r_max (e.g. 10 of 100 blocks against 0.1f) counts as inside the range */
+  float rate = (float)n_fallback / (float)n_blocks;
+  if (rate < r_min) return theta / alpha;
+  if (rate > r_max) return theta * alpha;
+  return theta;
+}
+
 /* Number of OpenMP threads fqo_gemm will use (1 when built without OpenMP). */
 #ifdef _OPENMP
 #include <omp.h>

@@ -40,6 +40,14 @@ def lib():
                                            C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int,
                                            C.c_int, C.c_void_p]
         _lib.fqo_num_threads.restype = C.c_int
+        _lib.fqo_philox4x32_10.restype = None
+        _lib.fqo_philox4x32_10.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        _lib.fqo_quantize_sr.restype = C.c_int
+        _lib.fqo_quantize_sr.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_long, C.c_int,
+                                         C.c_uint64, C.c_void_p, C.c_void_p]
+        _lib.fqo_threshold_update.restype = C.c_float
+        _lib.fqo_threshold_update.argtypes = [C.c_float, C.c_int, C.c_int, C.c_float, C.c_float,
+                                              C.c_float]
     return _lib
 
 
@@ -128,3 +136,29 @@ def gemm_partials(op, A: QTensor, B: QTensor, kb: int, residual_term: bool, wind
     if rc != 0:
         raise RuntimeError(f"fqo_gemm_partials failed: {rc}")
     return p
+
+
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, np.uint32)
+    k = np.asarray(key, np.uint32)
+    out = np.zeros(4, np.uint32)
+    lib().fqo_philox4x32_10(c.ctypes.data, k.ctypes.data, out.ctypes.data)
+    return out
+
+
+def quantize_sr(x_bf16: np.ndarray, g: int, seed: int) -> QTensor:
+    """Block INT8 with stochastic rounding (no fallback): Sec. 3.1 / 5.1."""
+    assert x_bf16.dtype == np.uint16 and x_bf16.ndim == 2 and x_bf16.strides[1] == 2
+    rows, cols = x_bf16.shape
+    ld = x_bf16.strides[0] // 2 if rows > 1 else max(cols, 1)
+    q = QTensor(rows, cols, g)
+    rc = lib().fqo_quantize_sr(x_bf16.ctypes.data, rows, cols, ld, g, C.c_uint64(seed),
+                               q.codes.ctypes.data, q.scales.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"fqo_quantize_sr failed: {rc}")
+    return q
+
+
+def threshold_update(theta, n_fallback, n_blocks, r_min=0.1, r_max=0.3, alpha=1.3) -> float:
+    return float(lib().fqo_threshold_update(C.c_float(theta), int(n_fallback), int(n_blocks),
+                                            C.c_float(r_min), C.c_float(r_max), C.c_float(alpha)))

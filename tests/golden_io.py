@@ -32,6 +32,8 @@ def load(name):
                 m = np.array([[float(t) for t in row] for row in rows], np.float64)
             elif kind == "i":
                 m = np.array([[int(t) for t in row] for row in rows], np.int64)
+            elif kind == "h":
+                m = np.array([[int(t, 16) for t in row] for row in rows], np.uint64)
             elif kind == "x":
                 m = np.array([[_hex_to_f32(t) for t in row] for row in rows], np.float32)
             else:
