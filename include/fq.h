@@ -149,6 +149,31 @@ fq_status fq_quantize(const void *x_bf16, int32_t rows, int32_t cols, int64_t ld
                       void *hip_stream);
 
 /*
+ * Block INT8 quantization with stochastic rounding (Sec. 3.1: x is rounded up with
+ * probability x - floor(x), so E[Q_s(x)] = x), the form the paper uses for the output
+ * gradient dY and for the stored activation context X (Sec. 5.1, 5.3).  No fallback:
+ * out->criterion becomes FQ_CRIT_NONE, mask is all 0, fb_count 0, every fb_slot -1.
+ * Same scale as fq_quantize (a = max|G|/127).  Element (r, c) draws its random word from
+ * the counter-based generator Philox4x32-10 with key `seed` and counter (r*cols + c) >> 2
+ * (output word (r*cols + c) & 3); with t = x/a in binary32 and u the word's top 24 bits,
+ * code = floor(t) + [u < (t - floor(t)) * 2^24], clamped to +-127.  Results depend only on
+ * (x, seed), not on launch shape, and `codes_t` holds the same draw transposed.
+ * Arguments, layouts and errors as fq_quantize (capacity may be 0).
+ */
+fq_status fq_quantize_sr(const void *x_bf16, int32_t rows, int32_t cols, int64_t ld,
+                         int32_t block, uint64_t seed, fq_qtensor *out, void *hip_stream);
+
+/*
+ * Delay Threshold (App. D, Alg. 2), host-only: the threshold a layer should use in the NEXT
+ * step given the fallback count its quantizer reported in this one (fq_qtensor_check).
+ * rate = n_fallback / n_blocks (binary32); returns theta / alpha if rate < r_min,
+ * theta * alpha if rate > r_max, theta otherwise (also when n_blocks <= 0).  The paper
+ * starts every layer at theta = 1 and uses [r_min, r_max] = [0.1, 0.3], alpha = 1.3.
+ */
+float fq_threshold_update(float theta, int32_t n_fallback, int32_t n_blocks, float r_min,
+                          float r_max, float alpha);
+
+/*
  * Fallback block GEMM (Alg. 1).  For every output tile, k-blocks ascending:
  *   C += float(P) * (a^A_ik * a^B_kj),  P the exact INT32 product of the code blocks,
  *   and, if u(i,k) = 1,  C += float(P~) * (a~^A_ik * a^B_kj)  with the residual

@@ -20,7 +20,8 @@ FQ_OUT_F32, FQ_OUT_BF16 = 0, 1
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfq.so")
 
-EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_gemm",
+EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr",
+           "fq_threshold_update", "fq_gemm",
            "fq_gemm_debug_partials", "fq_codes_to_rowmajor", "fq_qtensor_check",
            "fq_status_string"]
 
@@ -61,6 +62,12 @@ def lib():
         L.fq_quantize.restype = C.c_int
         L.fq_quantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int32, C.c_int,
                                   C.c_float, C.POINTER(fq_qtensor), C.c_void_p]
+        L.fq_quantize_sr.restype = C.c_int
+        L.fq_quantize_sr.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int32,
+                                     C.c_uint64, C.POINTER(fq_qtensor), C.c_void_p]
+        L.fq_threshold_update.restype = C.c_float
+        L.fq_threshold_update.argtypes = [C.c_float, C.c_int32, C.c_int32, C.c_float, C.c_float,
+                                          C.c_float]
         L.fq_gemm.restype = C.c_int
         L.fq_gemm.argtypes = [C.c_int, C.POINTER(fq_qtensor), C.POINTER(fq_qtensor), C.c_void_p,
                               C.c_int, C.c_int64, C.c_void_p]
@@ -159,6 +166,27 @@ def fq_quantize(x, crit, theta, out: QTensor = None, capacity=None, want_transpo
     _check(lib().fq_quantize(C.c_void_p(x.data_ptr()), rows, cols, ld, FQ_BLOCK, int(crit),
                              C.c_float(theta), C.byref(out.c), _stream_ptr(stream)), "fq_quantize")
     return out
+
+
+def fq_quantize_sr(x, seed, out: QTensor = None, want_transposed=False, stream=None) -> QTensor:
+    """Block INT8 with stochastic rounding (no fallback); x as for fq_quantize."""
+    import torch
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.is_cuda
+    assert x.stride(1) == 1 or x.shape[1] <= 1
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else max(cols, 1)
+    if out is None:
+        out = QTensor(rows, cols, 0, want_transposed, x.device)
+    _check(lib().fq_quantize_sr(C.c_void_p(x.data_ptr()), rows, cols, ld, FQ_BLOCK,
+                                C.c_uint64(seed), C.byref(out.c), _stream_ptr(stream)),
+           "fq_quantize_sr")
+    return out
+
+
+def fq_threshold_update(theta, n_fallback, n_blocks, r_min=0.1, r_max=0.3, alpha=1.3) -> float:
+    """Alg. 2 of the paper: next step's threshold from this step's fallback count (host only)."""
+    return float(lib().fq_threshold_update(C.c_float(theta), int(n_fallback), int(n_blocks),
+                                           C.c_float(r_min), C.c_float(r_max), C.c_float(alpha)))
 
 
 def gemm_out_shape(op, A: QTensor, B: QTensor):

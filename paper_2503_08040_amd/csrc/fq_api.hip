@@ -133,8 +133,10 @@ fq_status fq_qtensor_bind(void* base, int32_t rows, int32_t cols, int32_t block,
   return FQ_OK;
 }
 
-fq_status fq_quantize(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld, int32_t block,
-                      fq_criterion crit, float theta, fq_qtensor* out, void* hip_stream) {
+namespace {
+fq_status quantize_impl(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld, int32_t block,
+                        fq_criterion crit, float theta, int stochastic, uint64_t seed,
+                        fq_qtensor* out, void* hip_stream) {
   if (!out) return FQ_ERR_NULL;
   if (block != FQ_BLOCK) return FQ_ERR_BLOCK;
   if (rows < 0 || cols < 0 || ld < cols) return FQ_ERR_SHAPE;
@@ -153,6 +155,7 @@ fq_status fq_quantize(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld
   p.nbr = (int)ceil_div(rows, FQ_BLOCK); p.nbc = (int)ceil_div(cols, FQ_BLOCK);
   p.vec_ok = (((uintptr_t)x_bf16 & 15) == 0 && (ld % 8) == 0) ? 1 : 0;
   p.crit = (int)crit; p.theta = theta; p.capacity = out->capacity;
+  p.stochastic = stochastic; p.seed = seed;
   p.codes = out->codes; p.codes_t = out->codes_t;
   p.scales = out->scales; p.mask = out->mask;
   // Two alternating counters: this call counts in one and clears the other for the next call.
@@ -169,6 +172,26 @@ fq_status fq_quantize(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld
   if (fq::launch_quantize(p, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return FQ_ERR_HIP;
   return FQ_OK;
+}
+}  // namespace
+
+fq_status fq_quantize(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld, int32_t block,
+                      fq_criterion crit, float theta, fq_qtensor* out, void* hip_stream) {
+  return quantize_impl(x_bf16, rows, cols, ld, block, crit, theta, 0, 0, out, hip_stream);
+}
+
+fq_status fq_quantize_sr(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld, int32_t block,
+                         uint64_t seed, fq_qtensor* out, void* hip_stream) {
+  return quantize_impl(x_bf16, rows, cols, ld, block, FQ_CRIT_NONE, 0.0f, 1, seed, out, hip_stream);
+}
+
+float fq_threshold_update(float theta, int32_t n_fallback, int32_t n_blocks, float r_min,
+                          float r_max, float alpha) {
+  if (n_blocks <= 0) return theta;
+  const float rate = (float)n_fallback / (float)n_blocks;
+  if (rate < r_min) return theta / alpha;
+  if (rate > r_max) return theta * alpha;
+  return theta;
 }
 
 fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,

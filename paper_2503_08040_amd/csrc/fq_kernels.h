@@ -12,6 +12,8 @@ struct QuantParams {
   int nbr, nbc;
   int vec_ok;          // base 16-byte aligned and ld % 8 == 0: full blocks use 16-byte loads
   int crit;
+  int stochastic;      // 1: stochastic rounding with `seed` (crit must be 0)
+  uint64_t seed;
   float theta;
   int capacity;
   int8_t* codes;

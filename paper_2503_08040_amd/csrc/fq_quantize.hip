@@ -2,7 +2,8 @@
 // quantization, slot allocation and the compact list of flagged blocks in one
 // kernel launch, one pass over the bf16 input.
 //
-// Paper: Sec. 3.1 (a = max|G|/127, Q^ = round(G/a)), Sec. 4.4
+// Paper: Sec. 3.1 (a = max|G|/127, Q^ = round(G/a); round-to-nearest or, for gradients and
+// stored contexts, stochastic rounding, Sec. 5.1), Sec. 4.4
 // (u = [max|G| > theta]), Sec. 4.3 (second step on the residual G - a Q^),
 // Sec. 5.3 (the fallback decision is fused into the quantization kernel).
 //
@@ -41,6 +42,34 @@ __device__ inline int quantize_one(float x, float a) {
   return (int)t;
 }
 
+// Philox4x32-10 (Salmon et al., SC'11): counter (c0, c1, 0, 0), key (k0, k1).
+__device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1,
+                                     uint32_t (&out)[4]) {
+  uint32_t c2 = 0, c3 = 0;
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+    const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+    c0 = h1 ^ c1 ^ k0;
+    c1 = l1;
+    c2 = h0 ^ c3 ^ k1;
+    c3 = l0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Stochastic rounding of x/a with the 32-bit random word w: floor + [top 24 bits < fraction].
+__device__ inline int quantize_one_sr(float x, float a, uint32_t w) {
+  const float t = __fdiv_rn(x, a);
+  const float lo = floorf(t);
+  const float frac = t - lo;
+  float v = lo + (((float)(w >> 8) < frac * 16777216.0f) ? 1.0f : 0.0f);
+  v = fminf(fmaxf(v, -127.0f), 127.0f);
+  return (int)v;
+}
+
 __device__ inline v4i pack16(const int* q) {
   v4i o;
 #pragma unroll
@@ -71,7 +100,7 @@ __device__ inline void store_transposed(const int (&q)[4][16], int rp, int cc, i
 
 }  // namespace
 
-template <bool kWantT>
+template <bool kWantT, bool kStochastic>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
   __shared__ float red[4];
   __shared__ int slot_sh;
@@ -123,10 +152,38 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
   const float a = __fdiv_rn(amax, 127.0f);
 
   int q[4][16];
+  if (!kStochastic) {
 #pragma unroll
-  for (int pz = 0; pz < 4; ++pz)
+    for (int pz = 0; pz < 4; ++pz)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) q[pz][e] = (a == 0.0f) ? 0 : quantize_one(x[pz][e], a);
+      for (int e = 0; e < 16; ++e) q[pz][e] = (a == 0.0f) ? 0 : quantize_one(x[pz][e], a);
+  } else {
+    // element (r, c) uses word (r*cols + c) & 3 of the Philox block with counter (r*cols + c) >> 2
+    const uint32_t k0 = (uint32_t)p.seed, k1 = (uint32_t)(p.seed >> 32);
+#pragma unroll
+    for (int pz = 0; pz < 4; ++pz) {
+      const uint64_t e0 = (uint64_t)(row0 + pz * 32 + rp) * (uint64_t)p.cols + (uint64_t)col0;
+      if ((e0 & 3) == 0) {   // 16 columns = 4 whole Philox blocks
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          uint32_t w[4];
+          const uint64_t ctr = (e0 >> 2) + b;
+          philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), k0, k1, w);
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            q[pz][4 * b + i] = (a == 0.0f) ? 0 : quantize_one_sr(x[pz][4 * b + i], a, w[i]);
+        }
+      } else {               // row pitch not a multiple of 4: one block per element
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          uint32_t w[4];
+          const uint64_t el = e0 + e, ctr = el >> 2;
+          philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), k0, k1, w);
+          q[pz][e] = (a == 0.0f) ? 0 : quantize_one_sr(x[pz][e], a, w[el & 3]);
+        }
+      }
+    }
+  }
 
   int8_t* cdst = p.codes + (int64_t)blk * kBlockBytes;
 #pragma unroll
@@ -205,10 +262,16 @@ hipError_t launch_quantize(const QuantParams& p, hipStream_t st) {
     hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, st, p.fb_count, p.fb_count_next);
   const int nb = p.nbr * p.nbc;
   if (nb > 0) {
-    if (p.codes_t)
-      hipLaunchKernelGGL(quantize_kernel<true>, dim3(nb), dim3(kThreads), 0, st, p);
-    else
-      hipLaunchKernelGGL(quantize_kernel<false>, dim3(nb), dim3(kThreads), 0, st, p);
+    if (p.stochastic) {
+      if (p.codes_t)
+        hipLaunchKernelGGL((quantize_kernel<true, true>), dim3(nb), dim3(kThreads), 0, st, p);
+      else
+        hipLaunchKernelGGL((quantize_kernel<false, true>), dim3(nb), dim3(kThreads), 0, st, p);
+    } else if (p.codes_t) {
+      hipLaunchKernelGGL((quantize_kernel<true, false>), dim3(nb), dim3(kThreads), 0, st, p);
+    } else {
+      hipLaunchKernelGGL((quantize_kernel<false, false>), dim3(nb), dim3(kThreads), 0, st, p);
+    }
   }
   return hipGetLastError();
 }
