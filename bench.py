@@ -139,6 +139,41 @@ def sweep(args):
             "crossover_fraction_random": None if cross is None else round(cross, 3)}
 
 
+def backward(args):
+    """Sec. 5.1 / 5.3: dY is block-quantized with stochastic rounding, then two plain block GEMMs
+    dX = dY W and dW = dY^T X_ctx (X_ctx: the stochastic block-INT8 context stored in forward)."""
+    import torch
+    import paper_2503_08040_amd as fq
+    from paper_2503_08040_amd import synth
+    wl = make_workload(args.workload)
+    M, K, N = wl.M, wl.K, wl.N
+    rng = np.random.default_rng(1)
+    dy_bits = synth.to_bf16_bits((rng.standard_t(3.0, size=(M, N)) * 1e-3).astype(np.float32))
+    dy = torch.from_numpy(dy_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    x = torch.from_numpy(wl.X.view(np.int16)).cuda().view(torch.bfloat16)
+    w = torch.from_numpy(wl.W.view(np.int16)).cuda().view(torch.bfloat16)
+    qdy = fq.QTensor(M, N, capacity=0, want_transposed=True)
+    qw = fq.QTensor(N, K, capacity=0, want_transposed=True)
+    qx = fq.QTensor(M, K, capacity=0, want_transposed=True)
+    fq.fq_quantize(w, fq.FQ_CRIT_NONE, 0.0, out=qw)
+    fq.fq_quantize_sr(x, 5, out=qx)
+    dx = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
+    dw = torch.empty((N, K), dtype=torch.bfloat16, device="cuda")
+    ms_q = _time_loop(lambda: fq.fq_quantize_sr(dy, 7, out=qdy), 0.5, 50)
+    ms_dx = _time_loop(lambda: fq.fq_gemm(fq.FQ_OP_NN, qdy, qw, out=dx), 1.0, 50)
+    ms_dw = _time_loop(lambda: fq.fq_gemm(fq.FQ_OP_TN, qdy, qx, out=dw), 1.0, 50)
+    ms_bdx = _time_loop(lambda: torch.matmul(dy, w, out=dx), 1.0, 30)
+    ms_bdw = _time_loop(lambda: torch.matmul(dy.t(), x, out=dw), 1.0, 30)
+    ops = 2.0 * M * N * K
+    return {"workload": wl.name + "_backward", "ms_quantize_sr_dY": round(ms_q, 4),
+            "quantize_sr_gbs": round(4.0 * M * N / ms_q / 1e6, 1),
+            "ms_gemm_dX": round(ms_dx, 4), "tops_dX": round(ops / ms_dx / 1e9, 1),
+            "ms_gemm_dW": round(ms_dw, 4), "tops_dW": round(ops / ms_dw / 1e9, 1),
+            "effective_tops": round(2 * ops / (ms_q + ms_dx + ms_dw) / 1e9, 1),
+            "bf16_ms_dX": round(ms_bdx, 4), "bf16_ms_dW": round(ms_bdw, 4),
+            "speedup_vs_bf16": round((ms_bdx + ms_bdw) / (ms_q + ms_dx + ms_dw), 3)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -156,6 +191,9 @@ def main():
                          "crossover against the bf16 GEMM; prints one JSON object with a table")
     ap.add_argument("--no-mfma-ceiling", action="store_true",
                     help="skip the register-only MFMA throughput probe (about 3 s)")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the paper's backward recipe on the workload's shape instead: "
+                         "fq_quantize_sr(dY) + fq_gemm NN (dX) + fq_gemm TN (dW)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB (5 times) and exit: gives the "
                          "profiler's FETCH_SIZE / WRITE_SIZE counters a kernel of known traffic")
@@ -180,6 +218,9 @@ def main():
         return
     if args.sweep:
         print(json.dumps(sweep(args)), flush=True)
+        return
+    if args.backward:
+        print(json.dumps(backward(args)), flush=True)
         return
     log(f"[bench] generating {args.workload}")
     wl = make_workload(args.workload)

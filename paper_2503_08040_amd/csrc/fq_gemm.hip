@@ -93,35 +93,26 @@ __device__ __forceinline__ void pin(float& a, float& b, float& c, float& d) {
   asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
 }
 
-// INT32 -> FP32 without a convert instruction (v_cvt_f32_i32 issues at less than half the rate
-// of an FP32 add).  Every INT32 tile starts at the bit pattern of 1.5 * 2^23 instead of 0.  The
-// integer block product P satisfies |P| <= 128 * 127^2 < 2^22, so kMagicBits + P stays inside
-// the binade [2^23, 2^24), where one unit of the mantissa field is exactly 1.0: the MFMA result,
-// read as a float, is 12582912 + P exactly, and one FP32 subtraction gives float(P) exactly.
-constexpr int kMagicBits = 0x4B400000;
-constexpr float kMagicValue = 12582912.0f;
-
 // Per-wavefront register state of the k-loop.
 struct WaveState {
   float acc[4][2][16];   // FP32 accumulators: sub-tile (si, sj), 16 elements per lane
-  v4i aq[4];             // A fragments of the current si (ks = 0..3)
+  v4i aq[2][4];          // A fragments (ks = 0..3) of two consecutive si: si uses aq[si & 1]
   v4i bq[2][4];          // B fragments of this wave's two column groups
   v16i P[2];             // INT32 tiles: sub-tile u accumulates into P[u & 1]
   float T[4];            // elements converted in the previous slot, waiting for their FMA
-  v16i magic;            // 16 x 0x4B400000: start value of every INT32 tile (see kMagicBits)
-  float magicf;          // 12582912.0f in a vector register (a literal operand halves the rate)
 };
 
 // The k-loop is one continuous software pipeline over sub-tiles ("units": u = 2*si + sj, 8 per
 // item).  Unit u is 4 slots; slot g issues MFMA g (K = 32 of the 128) of unit u and, in the 32
 // cycles the matrix core needs for it, 8 vector-ALU instructions that fold the finished INT32
 // tile of unit u-1 into the FP32 accumulators: the 4 FMAs of the elements converted one slot
-// earlier, then the 4 INT32->FP32 conversions (one FP32 subtract each, see kMagicBits) of
-// elements 4g..4g+3.  An FMA never waits for its conversion, and a conversion reads an MFMA
-// result that is at least 11 issue slots old, as the hardware requires.
-// Fragment registers are refilled from LDS right after their last use: A fragments of the next
-// si inside the item, and in units 6 and 7 the B fragments and first A fragments of the NEXT
-// item, so that no item starts with a burst of LDS reads.  Scheduling fences pin this order.
+// earlier, then the 4 converts of elements 4g..4g+3.  An FMA never waits for its convert, and a
+// convert reads an MFMA result that is at least 11 issue slots old, as the hardware requires.
+// Fragment registers are refilled from LDS well before their next use: the A fragments of si+1
+// are fetched into a second register buffer while si is being multiplied (LDS latency under
+// load is several hundred cycles), and units 6 and 7 fetch the B fragments and the first A
+// fragments of the NEXT item, so that no item starts with a burst of LDS reads.  Scheduling
+// fences pin this order.
 //   a_cur: A pair of the current item in LDS; a_nxt / b_nxt: A pair / B block of the next item.
 //   s0, s1: scales of the current item's two i-blocks; sp: scale of the previous item's si = 3.
 template <int u>
@@ -132,15 +123,19 @@ __device__ __forceinline__ void run_unit(WaveState& st, const int8_t* a_cur, con
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     {
-      st.P[u & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(st.aq[g], st.bq[sj][g],
-                                                          g ? st.P[u & 1] : st.magic, 0, 0, 0);
-      if (u < 6 && sj == 1)
-        st.aq[g] = lds_frag(a_cur + ((si + 1) >> 1) * kBlockBytes, 2 * h + ((si + 1) & 1), g, lane);
-      if (u == 6) st.bq[0][g] = lds_frag(b_nxt, 2 * (jq & 1), g, lane);
-      if (u == 7) {
-        st.bq[1][g] = lds_frag(b_nxt, 2 * (jq & 1) + 1, g, lane);
-        st.aq[g] = lds_frag(a_nxt, 2 * h, g, lane);
+      const v16i z = {0};
+      st.P[u & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(st.aq[si & 1][g], st.bq[sj][g],
+                                                          g ? st.P[u & 1] : z, 0, 0, 0);
+      // A fragments of the next si (of the next item for si = 3) go into the other aq buffer
+      // a whole unit before their first use
+      if (u < 6 && sj == 0)
+        st.aq[(si + 1) & 1][g] =
+            lds_frag(a_cur + ((si + 1) >> 1) * kBlockBytes, 2 * h + ((si + 1) & 1), g, lane);
+      if (u == 6) {
+        st.aq[0][g] = lds_frag(a_nxt, 2 * h, g, lane);
+        st.bq[0][g] = lds_frag(b_nxt, 2 * (jq & 1), g, lane);
       }
+      if (u == 7) st.bq[1][g] = lds_frag(b_nxt, 2 * (jq & 1) + 1, g, lane);
       pin(st.P[u & 1]);
     }
     __builtin_amdgcn_sched_barrier(0);   // MFMA first: its destination must not alias live tiles
@@ -158,7 +153,7 @@ __device__ __forceinline__ void run_unit(WaveState& st, const int8_t* a_cur, con
     }
     __builtin_amdgcn_sched_barrier(0);   // FMAs before converts
 #pragma unroll
-    for (int i = 0; i < 4; ++i) st.T[i] = __int_as_float(st.P[(u - 1) & 1][4 * g + i]) - st.magicf;
+    for (int i = 0; i < 4; ++i) st.T[i] = (float)st.P[(u - 1) & 1][4 * g + i];
     pin(st.T[0], st.T[1], st.T[2], st.T[3]);
     __builtin_amdgcn_sched_barrier(0);
   }
@@ -173,7 +168,7 @@ __device__ __forceinline__ void drain(WaveState& st, float s1) {
     for (int i = 0; i < 4; ++i)
       st.acc[3][fsj][4 * fc + i] = __builtin_fmaf(st.T[i], s1, st.acc[3][fsj][4 * fc + i]);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) st.T[i] = __int_as_float(st.P[1][4 * g + i]) - st.magicf;
+    for (int i = 0; i < 4; ++i) st.T[i] = (float)st.P[1][4 * g + i];
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) st.acc[3][1][12 + i] = __builtin_fmaf(st.T[i], s1, st.acc[3][1][12 + i]);
@@ -308,16 +303,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
     __syncthreads();
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-      st.aq[g] = lds_frag(a_ring, 2 * h, g, lane);
+      st.aq[0][g] = lds_frag(a_ring, 2 * h, g, lane);
       st.bq[0][g] = lds_frag(b_ring + (jq >> 1) * kBlockBytes, 2 * (jq & 1), g, lane);
       st.bq[1][g] = lds_frag(b_ring + (jq >> 1) * kBlockBytes, 2 * (jq & 1) + 1, g, lane);
     }
-#pragma unroll
-    for (int i = 0; i < 16; ++i) st.magic[i] = kMagicBits;
-    st.magicf = kMagicValue;
-    // opaque to the optimizer: both stay in registers instead of being re-materialized
-    asm volatile("" : "+v"(st.magic), "+v"(st.magicf));
-    st.P[1] = st.magic;
+    st.P[1] = v16i{0};
 #pragma unroll
     for (int i = 0; i < 4; ++i) st.T[i] = 0.0f;
     float sp = 0.0f;                       // scale of the previous item's second i-block
