@@ -371,6 +371,72 @@ float fqo_threshold_update(float theta, int n_fallback, int n_blocks, float r_mi
   return theta;
 }
 
+/* ------------------------------------------------------------------------
+ * Activation-context compression for non-linear layers (Sec. 5.2, 5.3): the
+ * input of a normalization / activation function is kept for the backward pass
+ * as 10-bit integers with one scale per 1 x 128 group (one token, 128 channels),
+ * "5/8 of BF16", and dequantized again in the backward pass.
+ *   a = max|G| / 511,  q = round-to-nearest-even(x / a) in [-511, 511]  (Sec. 3.1 with L = 511;
+ *   the paper does not state the rounding of contexts: round-to-nearest is the reading here),
+ *   dequantized value = a * q, rounded to bf16 (the layers work in bf16).
+ * Packed format (not fixed by the paper): a group is 160 bytes, value i (two's complement,
+ * 10 bits) occupies bits [10 i, 10 i + 10) of the group's little-endian bit string; row r,
+ * group j starts at byte (r * ngroups + j) * 160; absent elements of a ragged last group are 0.
+ * Arithmetic in binary32 as for the block quantizer.
+ * ------------------------------------------------------------------------ */
+int fqo_ctx_quantize(const uint16_t *x_bf16, int rows, int cols, long ld, uint8_t *packed,
+                     float *scales) {
+  if (!x_bf16 || !packed || !scales) return -1;
+  if (rows < 0 || cols < 0 || ld < cols) return -2;
+  const int G = 128, ng = (cols + G - 1) / G;
+  for (int r = 0; r < rows; ++r)
+    for (int j = 0; j < ng; ++j) {
+      int c0 = j * G, c1 = c0 + G < cols ? c0 + G : cols;
+      float amax = 0.0f;
+      for (int c = c0; c < c1; ++c) {
+        float v = fabsf(bf16_to_f32(x_bf16[(size_t)r * ld + c]));
+        if (v > amax) amax = v;
+      }
+      float a = amax / 511.0f;
+      scales[(size_t)r * ng + j] = a;
+      uint8_t *dst = packed + ((size_t)r * ng + j) * 160;
+      memset(dst, 0, 160);
+      for (int c = c0; c < c1; ++c) {
+        int q = 0;
+        if (a != 0.0f) {
+          float t = rintf(bf16_to_f32(x_bf16[(size_t)r * ld + c]) / a);
+          if (t > 511.0f) t = 511.0f;
+          if (t < -511.0f) t = -511.0f;
+          q = (int)t;
+        }
+        uint32_t bits = (uint32_t)q & 0x3FFu;
+        int pos = (c - c0) * 10;
+        for (int b = 0; b < 10; ++b)
+          if (bits & (1u << b)) dst[(pos + b) >> 3] |= (uint8_t)(1u << ((pos + b) & 7));
+      }
+    }
+  return 0;
+}
+
+int fqo_ctx_dequantize(const uint8_t *packed, const float *scales, int rows, int cols,
+                       uint16_t *out_bf16, long ldo) {
+  if (!packed || !scales || !out_bf16) return -1;
+  if (rows < 0 || cols < 0 || ldo < cols) return -2;
+  const int G = 128, ng = (cols + G - 1) / G;
+  for (int r = 0; r < rows; ++r)
+    for (int c = 0; c < cols; ++c) {
+      int j = c / G, pos = (c - j * G) * 10;
+      const uint8_t *src = packed + ((size_t)r * ng + j) * 160;
+      uint32_t bits = 0;
+      for (int b = 0; b < 10; ++b)
+        if (src[(pos + b) >> 3] & (1u << ((pos + b) & 7))) bits |= 1u << b;
+      int q = (bits & 0x200u) ? (int)bits - 1024 : (int)bits;   /* sign-extend 10 bits */
+      float v = scales[(size_t)r * ng + j] * (float)q;
+      out_bf16[(size_t)r * ldo + c] = f32_to_bf16_rne(v);
+    }
+  return 0;
+}
+
 /* Number of OpenMP threads fqo_gemm will use (1 when built without OpenMP). */
 #ifdef _OPENMP
 #include <omp.h>

@@ -45,6 +45,12 @@ def lib():
         _lib.fqo_quantize_sr.restype = C.c_int
         _lib.fqo_quantize_sr.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_long, C.c_int,
                                          C.c_uint64, C.c_void_p, C.c_void_p]
+        _lib.fqo_ctx_quantize.restype = C.c_int
+        _lib.fqo_ctx_quantize.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_long, C.c_void_p,
+                                          C.c_void_p]
+        _lib.fqo_ctx_dequantize.restype = C.c_int
+        _lib.fqo_ctx_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
+                                            C.c_long]
         _lib.fqo_threshold_update.restype = C.c_float
         _lib.fqo_threshold_update.argtypes = [C.c_float, C.c_int, C.c_int, C.c_float, C.c_float,
                                               C.c_float]
@@ -162,3 +168,28 @@ def quantize_sr(x_bf16: np.ndarray, g: int, seed: int) -> QTensor:
 def threshold_update(theta, n_fallback, n_blocks, r_min=0.1, r_max=0.3, alpha=1.3) -> float:
     return float(lib().fqo_threshold_update(C.c_float(theta), int(n_fallback), int(n_blocks),
                                             C.c_float(r_min), C.c_float(r_max), C.c_float(alpha)))
+
+
+def ctx_quantize(x_bf16: np.ndarray):
+    """1 x 128 group INT10 context compression (Sec. 5.2): returns (packed uint8 [rows, ng, 160],
+    scales float32 [rows, ng])."""
+    assert x_bf16.dtype == np.uint16 and x_bf16.ndim == 2 and x_bf16.strides[1] == 2
+    rows, cols = x_bf16.shape
+    ld = x_bf16.strides[0] // 2 if rows > 1 else max(cols, 1)
+    ng = -(-cols // 128)
+    packed = np.zeros((rows, ng, 160), np.uint8)
+    scales = np.zeros((rows, ng), np.float32)
+    rc = lib().fqo_ctx_quantize(x_bf16.ctypes.data, rows, cols, ld, packed.ctypes.data,
+                                scales.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"fqo_ctx_quantize failed: {rc}")
+    return packed, scales
+
+
+def ctx_dequantize(packed: np.ndarray, scales: np.ndarray, rows: int, cols: int) -> np.ndarray:
+    out = np.zeros((rows, cols), np.uint16)
+    rc = lib().fqo_ctx_dequantize(packed.ctypes.data, scales.ctypes.data, rows, cols,
+                                  out.ctypes.data, max(cols, 1))
+    if rc != 0:
+        raise RuntimeError(f"fqo_ctx_dequantize failed: {rc}")
+    return out
