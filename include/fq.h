@@ -174,6 +174,34 @@ float fq_threshold_update(float theta, int32_t n_fallback, int32_t n_blocks, flo
                           float r_max, float alpha);
 
 /*
+ * INT10 compression of an activation context with 1 x 128 groups (Sec. 5.2: what a
+ * normalization or activation layer keeps for its backward pass is stored as 10-bit
+ * integers per 1 x 128 group, 5/8 of the bf16 bytes; Sec. 5.3: dequantized in backward).
+ * A row of `cols` values has ng = ceil(cols/128) groups; a group is the values that exist.
+ *   a = max|x| / 511 (binary32, correctly rounded division),
+ *   q = round-to-nearest-even(x / a) clamped to +-511 (0 when a = 0).
+ * packed: device, [rows*ng] records of FQ_CTX_GROUP_BYTES = 160 bytes, group (r, j) at
+ *   (r*ng + j)*160; value i of the group is the two's-complement field in bits
+ *   [10 i, 10 i + 10) of the record read as a little-endian bit string; fields of values
+ *   beyond `cols` are 0.  scales: device, float [rows*ng].
+ * fq_ctx_packed_bytes / fq_ctx_scales_bytes give the two buffer sizes (0 on invalid or
+ * overflowing shapes; host-only).  packed must be 4-byte aligned.
+ * Errors: FQ_ERR_NULL, FQ_ERR_SHAPE (rows/cols < 0, ld < cols, misaligned packed), FQ_ERR_HIP.
+ * rows == 0 or cols == 0 is valid and launches nothing.
+ */
+#define FQ_CTX_GROUP 128
+#define FQ_CTX_GROUP_BYTES 160
+size_t fq_ctx_packed_bytes(int32_t rows, int32_t cols);
+size_t fq_ctx_scales_bytes(int32_t rows, int32_t cols);
+fq_status fq_ctx_quantize(const void *x_bf16, int32_t rows, int32_t cols, int64_t ld,
+                          uint8_t *packed, float *scales, void *hip_stream);
+
+/* Inverse of fq_ctx_quantize: out_bf16[r, c] = RNE-bf16(a * q) (device, row-major
+ * [rows, ldo] bf16, ldo >= cols).  Same layouts and errors. */
+fq_status fq_ctx_dequantize(const uint8_t *packed, const float *scales, int32_t rows,
+                            int32_t cols, void *out_bf16, int64_t ldo, void *hip_stream);
+
+/*
  * Fallback block GEMM (Alg. 1).  For every output tile, k-blocks ascending:
  *   C += float(P) * (a^A_ik * a^B_kj),  P the exact INT32 product of the code blocks,
  *   and, if u(i,k) = 1,  C += float(P~) * (a~^A_ik * a^B_kj)  with the residual

@@ -10,6 +10,8 @@ import os
 
 FQ_BLOCK = 128
 FQ_BLOCK_BYTES = 16384
+FQ_CTX_GROUP = 128
+FQ_CTX_GROUP_BYTES = 160
 
 FQ_OK, FQ_ERR_NULL, FQ_ERR_SHAPE, FQ_ERR_BLOCK, FQ_ERR_ENUM, FQ_ERR_CAPACITY, FQ_ERR_HIP = \
     0, -1, -2, -3, -4, -5, -6
@@ -23,7 +25,8 @@ LIB_PATH = os.path.join(_HERE, "libfq.so")
 EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr",
            "fq_threshold_update", "fq_gemm",
            "fq_gemm_debug_partials", "fq_codes_to_rowmajor", "fq_qtensor_check",
-           "fq_status_string"]
+           "fq_status_string", "fq_ctx_packed_bytes", "fq_ctx_scales_bytes", "fq_ctx_quantize",
+           "fq_ctx_dequantize"]
 
 
 class fq_qtensor(C.Structure):
@@ -80,6 +83,15 @@ def lib():
         L.fq_qtensor_check.argtypes = [C.POINTER(fq_qtensor), C.POINTER(C.c_int32), C.c_void_p]
         L.fq_status_string.restype = C.c_char_p
         L.fq_status_string.argtypes = [C.c_int]
+        for f in (L.fq_ctx_packed_bytes, L.fq_ctx_scales_bytes):
+            f.restype = C.c_size_t
+            f.argtypes = [C.c_int32, C.c_int32]
+        L.fq_ctx_quantize.restype = C.c_int
+        L.fq_ctx_quantize.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_void_p,
+                                      C.c_void_p, C.c_void_p]
+        L.fq_ctx_dequantize.restype = C.c_int
+        L.fq_ctx_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                        C.c_int64, C.c_void_p]
         _lib = L
     return _lib
 
@@ -238,3 +250,48 @@ def fq_qtensor_check(t: QTensor, stream=None) -> int:
     n = C.c_int32(0)
     _check(lib().fq_qtensor_check(C.byref(t.c), C.byref(n), _stream_ptr(stream)), "fq_qtensor_check")
     return int(n.value)
+
+
+def fq_ctx_packed_bytes(rows, cols) -> int:
+    return int(lib().fq_ctx_packed_bytes(rows, cols))
+
+
+def fq_ctx_scales_bytes(rows, cols) -> int:
+    return int(lib().fq_ctx_scales_bytes(rows, cols))
+
+
+def fq_ctx_quantize(x, packed=None, scales=None, stream=None):
+    """1 x 128 group INT10 compression of a 2-D bf16 CUDA tensor (Sec. 5.2 of the paper).
+    Returns (packed uint8 [rows, ng, 160], scales float32 [rows, ng])."""
+    import torch
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.is_cuda
+    assert x.stride(1) == 1 or x.shape[1] <= 1
+    rows, cols = x.shape
+    ng = -(-cols // FQ_CTX_GROUP)
+    ld = x.stride(0) if rows > 1 else max(cols, 1)
+    if packed is None:
+        packed = torch.empty((rows, ng, FQ_CTX_GROUP_BYTES), dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty((rows, ng), dtype=torch.float32, device=x.device)
+    assert packed.is_contiguous() and packed.numel() == fq_ctx_packed_bytes(rows, cols)
+    assert scales.is_contiguous() and scales.numel() * 4 == fq_ctx_scales_bytes(rows, cols)
+    _check(lib().fq_ctx_quantize(C.c_void_p(x.data_ptr()), rows, cols, ld,
+                                 C.c_void_p(packed.data_ptr()), C.c_void_p(scales.data_ptr()),
+                                 _stream_ptr(stream)), "fq_ctx_quantize")
+    return packed, scales
+
+
+def fq_ctx_dequantize(packed, scales, rows, cols, out=None, stream=None):
+    """Inverse of fq_ctx_quantize: a bf16 [rows, cols] CUDA tensor."""
+    import torch
+    if out is None:
+        out = torch.empty((rows, cols), dtype=torch.bfloat16, device=packed.device)
+    assert out.dtype == torch.bfloat16 and out.shape == (rows, cols)
+    assert out.stride(1) == 1 or cols <= 1
+    assert packed.is_contiguous() and packed.numel() == fq_ctx_packed_bytes(rows, cols)
+    assert scales.is_contiguous() and scales.numel() * 4 == fq_ctx_scales_bytes(rows, cols)
+    ldo = out.stride(0) if rows > 1 else max(cols, 1)
+    _check(lib().fq_ctx_dequantize(C.c_void_p(packed.data_ptr()), C.c_void_p(scales.data_ptr()),
+                                   rows, cols, C.c_void_p(out.data_ptr()), ldo,
+                                   _stream_ptr(stream)), "fq_ctx_dequantize")
+    return out

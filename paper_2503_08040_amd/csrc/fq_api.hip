@@ -194,6 +194,57 @@ float fq_threshold_update(float theta, int32_t n_fallback, int32_t n_blocks, flo
   return theta;
 }
 
+namespace {
+// Number of 1 x 128 groups of a rows x cols context, or -1 if the shape is invalid or too
+// large for one launch.
+int64_t ctx_groups(int32_t rows, int32_t cols) {
+  if (rows < 0 || cols < 0) return -1;
+  const int64_t n = (int64_t)rows * ceil_div(cols, FQ_CTX_GROUP);
+  return n > ((int64_t)1 << 34) ? -1 : n;
+}
+
+fq_status ctx_impl(const void* x, int64_t ld, void* out, int64_t ldo, const uint8_t* packed,
+                   const float* scales, int32_t rows, int32_t cols, bool dequantize,
+                   void* hip_stream) {
+  const int64_t n = ctx_groups(rows, cols);
+  const int64_t pitch = dequantize ? ldo : ld;
+  const void* dense = dequantize ? out : x;
+  if (n < 0 || pitch < cols) return FQ_ERR_SHAPE;
+  if (n == 0) return FQ_OK;
+  if (!dense || !packed || !scales) return FQ_ERR_NULL;
+  if ((uintptr_t)packed & 3) return FQ_ERR_SHAPE;
+  fq::CtxParams p{};
+  p.x = static_cast<const uint16_t*>(x); p.ld = ld;
+  p.out = static_cast<uint16_t*>(out); p.ldo = ldo;
+  p.packed = const_cast<uint8_t*>(packed); p.scales = const_cast<float*>(scales);
+  p.cols = cols; p.ng = (int)ceil_div(cols, FQ_CTX_GROUP); p.n_groups = n;
+  p.vec_ok = (((uintptr_t)dense & 15) == 0 && (pitch % 8) == 0) ? 1 : 0;
+  if (fq::launch_ctx(p, dequantize, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return FQ_ERR_HIP;
+  return FQ_OK;
+}
+}  // namespace
+
+size_t fq_ctx_packed_bytes(int32_t rows, int32_t cols) {
+  const int64_t n = ctx_groups(rows, cols);
+  return n < 0 ? 0 : (size_t)n * FQ_CTX_GROUP_BYTES;
+}
+
+size_t fq_ctx_scales_bytes(int32_t rows, int32_t cols) {
+  const int64_t n = ctx_groups(rows, cols);
+  return n < 0 ? 0 : (size_t)n * sizeof(float);
+}
+
+fq_status fq_ctx_quantize(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld,
+                          uint8_t* packed, float* scales, void* hip_stream) {
+  return ctx_impl(x_bf16, ld, nullptr, 0, packed, scales, rows, cols, false, hip_stream);
+}
+
+fq_status fq_ctx_dequantize(const uint8_t* packed, const float* scales, int32_t rows,
+                            int32_t cols, void* out_bf16, int64_t ldo, void* hip_stream) {
+  return ctx_impl(nullptr, 0, out_bf16, ldo, packed, scales, rows, cols, true, hip_stream);
+}
+
 fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,
                   int64_t ldc, void* hip_stream) {
   fq::GemmParams g;

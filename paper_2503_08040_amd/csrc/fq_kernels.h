@@ -54,8 +54,25 @@ struct GemmParams {
   int debug_residual;         // debug mode: 0 main term, 1 residual term
 };
 
+// 1 x 128 group INT10 context compression (quantize: x -> packed, scales;
+// dequantize: packed, scales -> out).
+constexpr int kCtxGroup = 128;
+constexpr int kCtxGroupBytes = 160;
+struct CtxParams {
+  const uint16_t* x;   // bf16 bits, row-major [rows, ld]        (quantize)
+  int64_t ld;
+  uint16_t* out;       // bf16 bits, row-major [rows, ldo]       (dequantize)
+  int64_t ldo;
+  uint8_t* packed;     // [rows*ng][160]
+  float* scales;       // [rows*ng]
+  int cols, ng;
+  int64_t n_groups;    // rows * ng
+  int vec_ok;          // the bf16 side allows 16-byte accesses
+};
+
 hipError_t launch_quantize(const QuantParams& p, hipStream_t st);
 hipError_t launch_untile(const int8_t* tiled, int rows, int cols, int8_t* dense, hipStream_t st);
 hipError_t launch_gemm(const GemmParams& p, bool debug, hipStream_t st);
+hipError_t launch_ctx(const CtxParams& p, bool dequantize, hipStream_t st);
 
 }  // namespace fq
