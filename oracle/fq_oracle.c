@@ -15,6 +15,8 @@
  *   - two-step fallback quantization: quantize G, then quantize the residual
  *     dQ(G) = G - Q(G) with a scale of its own            : Sec. 4.3
  *   - fallback indicator u(i,k) = [max|G_ik| > theta]      : Sec. 4.4
+ *     (and the two error-based selectors the section compares it with:
+ *     L1 = sum|G - Q(G)| and L1-Rel = L1 / sum|G|, each against theta)
  *   - block GEMM, INT8 x INT8 -> INT32, dequantized by a^A * a^B and
  *     accumulated in FP32                                  : Sec. 4.2, Eq. (1)
  *   - fallback GEMM: k ascending; main term, then, if u(i,k)=1, the residual
@@ -56,6 +58,8 @@
 #define FQO_CRIT_NONE 0      /* u == 0 everywhere: plain block INT8, Eq. (1) */
 #define FQO_CRIT_ABSMAX_GT 1 /* u = [max|G| > theta], Sec. 4.4            */
 #define FQO_CRIT_ALL 2       /* u == 1 everywhere                           */
+#define FQO_CRIT_L1_GT 3     /* u = [sum|G - Q(G)| > theta], Sec. 4.4       */
+#define FQO_CRIT_L1REL_GT 4  /* u = [sum|G - Q(G)| / sum|G| > theta], Sec. 4.4 */
 
 #define FQO_OP_NT 0 /* C[M,N] = A[M,K] * B[N,K]^T   (Y  = X  W^T) */
 #define FQO_OP_NN 1 /* C[M,K] = A[M,N] * B[N,K]     (dX = dY W)   */
@@ -93,7 +97,7 @@ int fqo_quantize(const uint16_t *x_bf16, int rows, int cols, long ld, int g,
       !fb_list || !fb_count)
     return -1;
   if (rows < 0 || cols < 0 || g < 1 || ld < cols) return -2;
-  if (crit < 0 || crit > 2) return -4;
+  if (crit < 0 || crit > 4) return -4;
   int nbr = (rows + g - 1) / g, nbc = (cols + g - 1) / g;
   int n_fb = 0;
   for (int bi = 0; bi < nbr; ++bi) {
@@ -118,7 +122,21 @@ int fqo_quantize(const uint16_t *x_bf16, int rows, int cols, long ld, int g,
       int u;
       if (crit == FQO_CRIT_NONE) u = 0;
       else if (crit == FQO_CRIT_ALL) u = 1;
-      else u = (amax > theta) ? 1 : 0;
+      else if (crit == FQO_CRIT_ABSMAX_GT) u = (amax > theta) ? 1 : 0;
+      else {
+        /* block quantization error L1 = sum |G - Q(G)| and sum |G|, summed in binary64 over
+         * the binary32 residuals (the same residual the second step quantizes) */
+        double l1 = 0.0, l1x = 0.0;
+        for (int r = r0; r < r1; ++r)
+          for (int c = c0; c < c1; ++c) {
+            float x = bf16_to_f32(x_bf16[(size_t)r * ld + c]);
+            float res = fmaf(-(float)codes[(size_t)r * cols + c], a, x);
+            l1 += (double)fabsf(res);
+            l1x += (double)fabsf(x);
+          }
+        if (crit == FQO_CRIT_L1_GT) u = (l1 > (double)theta) ? 1 : 0;
+        else u = (l1x > 0.0 && l1 / l1x > (double)theta) ? 1 : 0; /* all-zero block: never flagged */
+      }
       mask[bi * nbc + bk] = (uint8_t)u;
       /* step 2 (flagged blocks only): quantize the residual G - Q(G) */
       float ra = 0.0f;

@@ -11,7 +11,7 @@ import numpy as np
 
 from . import build as _build
 
-CRIT_NONE, CRIT_ABSMAX_GT, CRIT_ALL = 0, 1, 2
+CRIT_NONE, CRIT_ABSMAX_GT, CRIT_ALL, CRIT_L1_GT, CRIT_L1REL_GT = 0, 1, 2, 3, 4
 OP_NT, OP_NN, OP_TN = 0, 1, 2
 
 
