@@ -68,8 +68,20 @@ typedef enum {
 } fq_status;
 
 /* Fallback criterion.  NONE: u = 0 everywhere (plain block INT8, Eq. (1)).
- * ABSMAX_GT: u(i,k) = [max|G_ik| > theta], strict (Sec. 4.4).  ALL: u = 1. */
-typedef enum { FQ_CRIT_NONE = 0, FQ_CRIT_ABSMAX_GT = 1, FQ_CRIT_ALL = 2 } fq_criterion;
+ * ABSMAX_GT: u(i,k) = [max|G_ik| > theta], strict; the selector the paper adopts (Sec. 4.4).
+ * ALL: u = 1.
+ * L1_GT, L1REL_GT: the two error-based selectors Sec. 4.4 compares it with,
+ *   u = [L1 > theta] with L1 = sum |G_ik - Q(G_ik)| over the block, and
+ *   u = [L1 / sum |G_ik| > theta] (an all-zero block is never flagged).
+ *   G - Q(G) is the same binary32 residual the second quantization step uses; the two sums
+ *   are binary64 accumulations of the binary32 terms in unspecified order and the comparison
+ *   is binary64, so a block whose metric is within about 2^-40 (relative) of theta may be
+ *   decided either way.  These two cost one extra pass over the block in registers.
+ * (Selecting the top-k blocks of a tensor needs a tensor-wide reduction; the paper replaces
+ * it by the delayed threshold of App. D, see fq_threshold_update.) */
+typedef enum {
+  FQ_CRIT_NONE = 0, FQ_CRIT_ABSMAX_GT = 1, FQ_CRIT_ALL = 2, FQ_CRIT_L1_GT = 3, FQ_CRIT_L1REL_GT = 4
+} fq_criterion;
 
 /* Which product of the linear layer (Sec. 3.2).  A is the operand that may
  * carry fallback blocks (Alg. 1 defines fallback for A only).

@@ -15,7 +15,7 @@ FQ_CTX_GROUP_BYTES = 160
 
 FQ_OK, FQ_ERR_NULL, FQ_ERR_SHAPE, FQ_ERR_BLOCK, FQ_ERR_ENUM, FQ_ERR_CAPACITY, FQ_ERR_HIP = \
     0, -1, -2, -3, -4, -5, -6
-FQ_CRIT_NONE, FQ_CRIT_ABSMAX_GT, FQ_CRIT_ALL = 0, 1, 2
+FQ_CRIT_NONE, FQ_CRIT_ABSMAX_GT, FQ_CRIT_ALL, FQ_CRIT_L1_GT, FQ_CRIT_L1REL_GT = 0, 1, 2, 3, 4
 FQ_OP_NT, FQ_OP_NN, FQ_OP_TN = 0, 1, 2
 FQ_OUT_F32, FQ_OUT_BF16 = 0, 1
 

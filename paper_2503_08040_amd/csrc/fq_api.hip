@@ -57,9 +57,7 @@ fq_status prepare_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, fq::G
   if (s != FQ_OK) return s;
   if (op != FQ_OP_NT && op != FQ_OP_NN && op != FQ_OP_TN) return FQ_ERR_ENUM;
   if (B->criterion != FQ_CRIT_NONE) return FQ_ERR_ENUM;
-  if (A->criterion != FQ_CRIT_NONE && A->criterion != FQ_CRIT_ABSMAX_GT &&
-      A->criterion != FQ_CRIT_ALL)
-    return FQ_ERR_ENUM;
+  if (A->criterion < FQ_CRIT_NONE || A->criterion > FQ_CRIT_L1REL_GT) return FQ_ERR_ENUM;
   const bool a_fb = A->criterion != FQ_CRIT_NONE;
   if (a_fb && A->capacity == 0) return FQ_ERR_CAPACITY;
   const int a_nbr = (int)ceil_div(A->rows, FQ_BLOCK), a_nbc = (int)ceil_div(A->cols, FQ_BLOCK);
@@ -140,8 +138,7 @@ fq_status quantize_impl(const void* x_bf16, int32_t rows, int32_t cols, int64_t 
   if (!out) return FQ_ERR_NULL;
   if (block != FQ_BLOCK) return FQ_ERR_BLOCK;
   if (rows < 0 || cols < 0 || ld < cols) return FQ_ERR_SHAPE;
-  if (crit != FQ_CRIT_NONE && crit != FQ_CRIT_ABSMAX_GT && crit != FQ_CRIT_ALL)
-    return FQ_ERR_ENUM;
+  if (crit < FQ_CRIT_NONE || crit > FQ_CRIT_L1REL_GT) return FQ_ERR_ENUM;
   fq_status s = check_qtensor(out);
   if (s != FQ_OK) return s;
   if (out->rows != rows || out->cols != cols) return FQ_ERR_SHAPE;

@@ -35,6 +35,23 @@ __device__ inline float block_max(float v, float* red) {
   return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
+// sums of two binary64 values over the workgroup; every thread gets both.  red: 8 doubles.
+__device__ inline void block_sum2(double& a, double& b, double* red) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    a += __shfl_xor(a, off, 64);
+    b += __shfl_xor(b, off, 64);
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) {
+    red[threadIdx.x >> 6] = a;
+    red[4 + (threadIdx.x >> 6)] = b;
+  }
+  __syncthreads();
+  a = (red[0] + red[1]) + (red[2] + red[3]);
+  b = (red[4] + red[5]) + (red[6] + red[7]);
+}
+
 // round-to-nearest-even of x/a with a correctly rounded division, clamped.
 __device__ inline int quantize_one(float x, float a) {
   float t = rintf(__fdiv_rn(x, a));
@@ -100,9 +117,12 @@ __device__ inline void store_transposed(const int (&q)[4][16], int rp, int cc, i
 
 }  // namespace
 
-template <bool kWantT, bool kStochastic>
+// kErr: the fallback decision uses a block quantization-error metric (criteria 3, 4), which
+// needs the residual of every block, not only of the flagged ones.
+template <bool kWantT, bool kStochastic, bool kErr>
 __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
   __shared__ float red[4];
+  __shared__ double redd[kErr ? 8 : 1];
   __shared__ int slot_sh;
   __shared__ __attribute__((aligned(16))) int8_t img[kWantT ? kBlockBytes : 16];
 
@@ -194,7 +214,22 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
 
   // ---- fallback decision                                         (Sec. 4.4)
   bool u;
-  if (p.crit == 0) u = false;
+  if (kErr) {
+    // L1 = sum |G - Q(G)| over the block, L1-Rel = L1 / sum |G|; the sums are binary64
+    // accumulations of the binary32 terms (order unspecified), compared with theta in binary64
+    double l1 = 0.0, l1x = 0.0;
+#pragma unroll
+    for (int pz = 0; pz < 4; ++pz)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        l1x += (double)fabsf(x[pz][e]);
+        x[pz][e] = __builtin_fmaf(-(float)q[pz][e], a, x[pz][e]);
+        l1 += (double)fabsf(x[pz][e]);
+      }
+    block_sum2(l1, l1x, redd);
+    if (p.crit == 3) u = l1 > (double)p.theta;
+    else u = l1x > 0.0 && l1 / l1x > (double)p.theta;
+  } else if (p.crit == 0) u = false;
   else if (p.crit == 2) u = true;
   else u = amax > p.theta;
 
@@ -222,7 +257,7 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
   for (int pz = 0; pz < 4; ++pz)
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      x[pz][e] = __builtin_fmaf(-(float)q[pz][e], a, x[pz][e]);
+      if (!kErr) x[pz][e] = __builtin_fmaf(-(float)q[pz][e], a, x[pz][e]);
       rm = fmaxf(rm, fabsf(x[pz][e]));
     }
   const float rmax = block_max(rm, red);
@@ -262,15 +297,17 @@ hipError_t launch_quantize(const QuantParams& p, hipStream_t st) {
     hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, st, p.fb_count, p.fb_count_next);
   const int nb = p.nbr * p.nbc;
   if (nb > 0) {
+    const dim3 grid(nb), block(kThreads);
+    const bool err = p.crit >= 3;
     if (p.stochastic) {
-      if (p.codes_t)
-        hipLaunchKernelGGL((quantize_kernel<true, true>), dim3(nb), dim3(kThreads), 0, st, p);
-      else
-        hipLaunchKernelGGL((quantize_kernel<false, true>), dim3(nb), dim3(kThreads), 0, st, p);
-    } else if (p.codes_t) {
-      hipLaunchKernelGGL((quantize_kernel<true, false>), dim3(nb), dim3(kThreads), 0, st, p);
+      if (p.codes_t) hipLaunchKernelGGL((quantize_kernel<true, true, false>), grid, block, 0, st, p);
+      else hipLaunchKernelGGL((quantize_kernel<false, true, false>), grid, block, 0, st, p);
+    } else if (err) {
+      if (p.codes_t) hipLaunchKernelGGL((quantize_kernel<true, false, true>), grid, block, 0, st, p);
+      else hipLaunchKernelGGL((quantize_kernel<false, false, true>), grid, block, 0, st, p);
     } else {
-      hipLaunchKernelGGL((quantize_kernel<false, false>), dim3(nb), dim3(kThreads), 0, st, p);
+      if (p.codes_t) hipLaunchKernelGGL((quantize_kernel<true, false, false>), grid, block, 0, st, p);
+      else hipLaunchKernelGGL((quantize_kernel<false, false, false>), grid, block, 0, st, p);
     }
   }
   return hipGetLastError();
