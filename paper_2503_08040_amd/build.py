@@ -15,20 +15,25 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Wall", "-Wno-unused-command-line-argument"]
 
 
-TOOL_SRC = os.path.join(CSRC, "tools", "mfma_ceiling.hip")
+TOOLS = ["mfma_ceiling", "group_size_probe"]
 TOOL_BIN = os.path.join(HERE, "mfma_ceiling")
 
 
-def build_tools() -> str:
-    """The register-only MFMA throughput probe used for the benchmark's roofline context."""
+def build_tools() -> list:
+    """Register-only throughput probes (measurement support for the benchmark's roofline
+    context): one executable per source under csrc/tools, placed next to the library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature",
-           "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-o", TOOL_BIN,
-           TOOL_SRC]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError(f"hipcc failed:\n{r.stderr}")
-    return TOOL_BIN
+    out = []
+    for name in TOOLS:
+        exe = os.path.join(HERE, name)
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature",
+               "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument", "-o", exe,
+               os.path.join(CSRC, "tools", name + ".hip")]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed:\n{r.stderr}")
+        out.append(exe)
+    return out
 
 
 def stale() -> bool:
