@@ -174,6 +174,33 @@ def backward(args):
             "speedup_vs_bf16": round((ms_bdx + ms_bdw) / (ms_q + ms_dx + ms_dw), 3)}
 
 
+def context(args):
+    """Sec. 5.2 / 5.3: 1 x 128 group INT10 compression of a non-linear layer's activation context
+    (the workload's X: for cfg3 the SiLU-GLU output fed to the down projection) and its
+    dequantization, each against the HBM roofline."""
+    import torch
+    import paper_2503_08040_amd as fq
+    wl = make_workload(args.workload)
+    x = torch.from_numpy(wl.X.view(np.int16)).cuda().view(torch.bfloat16)
+    rows, cols = x.shape
+    packed, scales = fq.fq_ctx_quantize(x)
+    back = torch.empty_like(x)
+    ms_q = _time_loop(lambda: fq.fq_ctx_quantize(x, packed, scales), 1.0, 100)
+    ms_d = _time_loop(lambda: fq.fq_ctx_dequantize(packed, scales, rows, cols, out=back), 1.0, 100)
+    ms_c = _time_loop(lambda: back.copy_(x), 1.0, 100)
+    nbytes = 2.0 * rows * cols + packed.numel() + 4.0 * scales.numel()
+    return {"workload": wl.name + "_context_int10", "rows": rows, "cols": cols,
+            "bytes_bf16": 2 * rows * cols, "bytes_int10": packed.numel() + 4 * scales.numel(),
+            "ms_quantize": round(ms_q, 5), "ms_dequantize": round(ms_d, 5),
+            "roofline_quantize": {"bound": "hbm", "achieved": round(nbytes / ms_q / 1e6, 1),
+                                  "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                  "frac": round(nbytes / ms_q / 1e6 / HBM_PEAK_GBS, 4)},
+            "roofline_dequantize": {"bound": "hbm", "achieved": round(nbytes / ms_d / 1e6, 1),
+                                    "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                    "frac": round(nbytes / ms_d / 1e6 / HBM_PEAK_GBS, 4)},
+            "bf16_copy_gbs": round(4.0 * rows * cols / ms_c / 1e6, 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -194,6 +221,9 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="time the paper's backward recipe on the workload's shape instead: "
                          "fq_quantize_sr(dY) + fq_gemm NN (dX) + fq_gemm TN (dW)")
+    ap.add_argument("--context", action="store_true",
+                    help="time the INT10 1x128 context compression / decompression of the "
+                         "workload's X instead (GB/s against the HBM roofline)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB (5 times) and exit: gives the "
                          "profiler's FETCH_SIZE / WRITE_SIZE counters a kernel of known traffic")
@@ -221,6 +251,9 @@ def main():
         return
     if args.backward:
         print(json.dumps(backward(args)), flush=True)
+        return
+    if args.context:
+        print(json.dumps(context(args)), flush=True)
         return
     log(f"[bench] generating {args.workload}")
     wl = make_workload(args.workload)
