@@ -230,6 +230,20 @@ fq_status fq_ctx_dequantize(const uint8_t *packed, const float *scales, int32_t 
 fq_status fq_gemm(fq_op op, const fq_qtensor *A, const fq_qtensor *B, void *C,
                   fq_out_dtype cdt, int64_t ldc, void *hip_stream);
 
+/*
+ * How fq_gemm cuts an rows_out x cols_out output into workgroup tiles (host-only inspection;
+ * App. C: the GEMM tile need not equal the quantization block).  The output is covered by
+ * 256 x 256 tiles (2 x 2 quantization blocks); when their number would leave the last round of
+ * the GPU's compute units mostly idle, the last block columns are covered by 128 x 384 tiles
+ * (1 x 3 blocks) instead.  plan[0] = workgroups with 256 x 256 tiles, plan[1] = tile columns
+ * they cover, plan[2] = columns of 128 x 384 tiles (0: none).  compute_units <= 0 means the
+ * current device's count, or the value of the environment variable FQ_GEMM_CUS if that is set
+ * to a positive number (fq_gemm reads the same variable; meant for tuning and tests).  The
+ * plan never changes results: every output element is accumulated in Alg. 1's order.
+ */
+fq_status fq_gemm_tile_plan(int32_t rows_out, int32_t cols_out, int32_t compute_units,
+                            int32_t plan[3]);
+
 /* The INT32 block product of k-block `k_block` alone (Alg. 1's INT x INT
  * product before dequantization): main term (residual_term = 0) or residual
  * term (1; zero for unflagged blocks).  p_out: device int32 [Mout, Nout]

@@ -26,7 +26,7 @@ EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr
            "fq_threshold_update", "fq_gemm",
            "fq_gemm_debug_partials", "fq_codes_to_rowmajor", "fq_qtensor_check",
            "fq_status_string", "fq_ctx_packed_bytes", "fq_ctx_scales_bytes", "fq_ctx_quantize",
-           "fq_ctx_dequantize"]
+           "fq_ctx_dequantize", "fq_gemm_tile_plan"]
 
 
 class fq_qtensor(C.Structure):
@@ -92,6 +92,8 @@ def lib():
         L.fq_ctx_dequantize.restype = C.c_int
         L.fq_ctx_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                         C.c_int64, C.c_void_p]
+        L.fq_gemm_tile_plan.restype = C.c_int
+        L.fq_gemm_tile_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         _lib = L
     return _lib
 
@@ -295,3 +297,11 @@ def fq_ctx_dequantize(packed, scales, rows, cols, out=None, stream=None):
                                    rows, cols, C.c_void_p(out.data_ptr()), ldo,
                                    _stream_ptr(stream)), "fq_ctx_dequantize")
     return out
+
+
+def fq_gemm_tile_plan(rows_out, cols_out, compute_units=0):
+    """(workgroups with 256x256 tiles, tile columns they cover, columns of 128x384 tiles)."""
+    out = (C.c_int32 * 3)()
+    _check(lib().fq_gemm_tile_plan(int(rows_out), int(cols_out), int(compute_units), out),
+           "fq_gemm_tile_plan")
+    return int(out[0]), int(out[1]), int(out[2])

@@ -259,6 +259,17 @@ fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, f
   return FQ_OK;
 }
 
+fq_status fq_gemm_tile_plan(int32_t rows_out, int32_t cols_out, int32_t compute_units,
+                            int32_t plan[3]) {
+  if (!plan) return FQ_ERR_NULL;
+  if (rows_out < 0 || cols_out < 0) return FQ_ERR_SHAPE;
+  int out[3];
+  fq::gemm_tile_plan((int)ceil_div(rows_out, FQ_BLOCK), (int)ceil_div(cols_out, FQ_BLOCK),
+                     compute_units, out);
+  plan[0] = out[0]; plan[1] = out[1]; plan[2] = out[2];
+  return FQ_OK;
+}
+
 fq_status fq_gemm_debug_partials(fq_op op, const fq_qtensor* A, const fq_qtensor* B,
                                  int32_t k_block, int residual_term, int32_t* p_out,
                                  void* hip_stream) {

@@ -8,28 +8,32 @@
 //
 // Shape of the kernel (differs from the paper's 128^3 CUDA tile on purpose):
 //   - workgroup = 8 wavefronts (2 per SIMD), output tile 256 x 256 = 2 x 2
-//     quantization blocks.  Wavefront (h, jq) owns rows [64h, 64h+64) of BOTH
-//     i-blocks and the 64-column quarter jq of the tile: 4 x 2 sub-tiles of
+//     quantization blocks.  Wavefront (h, c) owns rows [64h, 64h+64) of BOTH
+//     i-blocks and the 64-column quarter c of the tile: 4 x 2 sub-tiles of
 //     32 x 32, 128 FP32 accumulators per lane in architectural VGPRs (the
 //     vector ALU cannot read accumulation registers, so the accumulators it
-//     updates must not live there);
+//     updates must not live there).  A second geometry, 1 x 3 blocks
+//     (128 x 384, 2 x 3 sub-tiles per wavefront), covers the last block columns
+//     when the 2 x 2 tiles would leave the final round of the chip mostly idle;
 //   - the k-loop runs over "items": the main product of k-block k and, when
-//     one of the tile's two A blocks is flagged at k, a residual item right
+//     one of the tile's A blocks is flagged at k, a residual item right
 //     after it.  A and B operands sit in two independent double-buffered LDS
-//     rings (2 x 32 KiB each): an item always brings a new A pair (codes or
-//     residual codes), a new B pair only when k advances, so the residual
+//     rings (64 KiB each for 2 x 2): an item always brings a new A set (codes or
+//     residual codes), a new B set only when k advances, so the residual
 //     product re-uses the B blocks already on chip exactly as Alg. 1 says.
-//     Because every wavefront spans both i-blocks, a residual item costs each
-//     wavefront work in proportion to the number of flagged blocks: the
-//     overhead is proportional to the fallback rate;
+//     Because every wavefront spans all i-blocks of the tile, a residual item
+//     loads every wavefront equally;
 //   - operands reach LDS by direct global->LDS 16-byte loads (blocks are stored
 //     in operand order, see fq.h), one barrier per item;
 //   - per 32 x 32 sub-tile: 4 v_mfma_i32_32x32x32_i8 (K = 128) into an INT32
 //     tile, then one convert + one FMA per element folds it into the FP32
 //     accumulators with the scalar scale of that block pair.
 // The accumulation order per output element is exactly Alg. 1's (k ascending,
-// main term then residual term), so results match a sequential evaluation
-// bit for bit.
+// main term then residual term) in both geometries, so results match a
+// sequential evaluation bit for bit and do not depend on the tile plan.
+#include <algorithm>
+#include <cstdlib>
+
 #include "fq_device.h"
 #include "fq_kernels.h"
 
@@ -41,10 +45,8 @@ constexpr int kThreads = 512;
 constexpr int kXcds = 8;      // accelerator complex dies, each with a private L2
 constexpr int kGroupN = 4;    // tile columns per rasterization group
 constexpr int kRingBytes = 2 * kBlockBytes;     // one A pair or one B pair
-constexpr int kStagePitch = 72;                 // floats per row of the epilogue staging patch
-constexpr int kStageBytesPerWave = 64 * kStagePitch * 4;
-constexpr int kLdsBytes = 8 * kStageBytesPerWave;   // 144 KiB: covers the rings (A x2, B x2 = 128 KiB)
-static_assert(kLdsBytes >= 4 * kRingBytes, "LDS must hold both operand rings");
+constexpr int kLdsBytes = 4 * kRingBytes;       // 128 KiB: two A sets + two B sets; the epilogue
+                                                // staging patches re-use the same memory
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef const __attribute__((address_space(1))) void gbl_void;
@@ -93,58 +95,109 @@ __device__ __forceinline__ void pin(float& a, float& b, float& c, float& d) {
   asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
 }
 
-// Per-wavefront register state of the k-loop.
-struct WaveState {
-  float acc[4][2][16];   // FP32 accumulators: sub-tile (si, sj), 16 elements per lane
-  v4i aq[2][4];          // A fragments (ks = 0..3) of two consecutive si: si uses aq[si & 1]
-  v4i bq[2][4];          // B fragments of this wave's two column groups
-  v16i P[2];             // INT32 tiles: sub-tile u accumulates into P[u & 1]
-  float T[4];            // elements converted in the previous slot, waiting for their FMA
+// Geometry of a workgroup tile: kBI x kBJ quantization blocks, computed by 8 wavefronts laid
+// out 2 (row halves h) x 4 (column groups c).  Wavefront (h, c) owns rows [64h, 64h+64) of every
+// i-block of the tile and the 32*kBJ columns starting at 32*kBJ*c: kSI x kSJ sub-tiles of
+// 32 x 32.  Two geometries are used: 2 x 2 blocks (256 x 256, 8 sub-tiles per wavefront) for
+// the bulk of the output and 1 x 3 blocks (128 x 384, 6 sub-tiles) for the columns left over
+// when the 2 x 2 tiles do not fill a whole number of rounds of the chip (see launch_gemm).
+template <int kBI_, int kBJ_>
+struct Geo {
+  static constexpr int kBI = kBI_, kBJ = kBJ_;
+  static constexpr int kSI = 2 * kBI;        // 32-row groups per wavefront
+  static constexpr int kSJ = kBJ;            // 32-column groups per wavefront
+  static constexpr int kUnits = kSI * kSJ;   // sub-tiles per wavefront and item
+  static constexpr int kASet = kBI * kBlockBytes;   // the A blocks of one item in LDS
+  static constexpr int kBSet = kBJ * kBlockBytes;   // the B blocks of one k-block in LDS
+  // A wavefront's columns lie in one j-block when kBJ = 2 and in up to two when kBJ = 3, so the
+  // scale of a sub-tile depends on sj only in the second case.
+  static constexpr int kSC = (kBJ == 2) ? 1 : kSJ;  // distinct scale columns per i-block
+  static constexpr int kSP = (kBJ == 2) ? 1 : 2;    // distinct scales of an item's last two units
+  static constexpr int kStageCols = 32 * kSJ;
+  static constexpr int kStagePitch = kStageCols + 8;   // floats per staged row: conflict-free
+  static constexpr int kStageBytesPerWave = 32 * kStagePitch * 4;
+  static_assert(2 * (kASet + kBSet) <= kLdsBytes, "operand rings must fit");
+  static_assert(8 * kStageBytesPerWave <= kLdsBytes, "epilogue staging must fit");
+  static_assert(kBI + kBJ == 4, "8 wavefronts stage 8 half-blocks per item");
 };
 
-// The k-loop is one continuous software pipeline over sub-tiles ("units": u = 2*si + sj, 8 per
-// item).  Unit u is 4 slots; slot g issues MFMA g (K = 32 of the 128) of unit u and, in the 32
+// Per-wavefront register state of the k-loop.
+template <class G>
+struct WaveState {
+  float acc[G::kSI][G::kSJ][16];   // FP32 accumulators: sub-tile (si, sj), 16 elements per lane
+  v4i aq[2][4];                    // A fragments (ks = 0..3) of two consecutive si: si uses aq[si & 1]
+  v4i bq[G::kSJ][4];               // B fragments of this wave's column groups
+  v16i P[2];                       // INT32 tiles: sub-tile u accumulates into P[u & 1]
+  float T[4];                      // elements converted in the previous slot, waiting for their FMA
+};
+
+// Scales of one item as the units see them: s[bi][sc] = a^A (or a~^A) of i-block bi times a^B
+// of the j-block that scale column sc lies in.
+template <class G>
+struct ItemScales {
+  float s[G::kBI][G::kSC];
+};
+
+// The k-loop is one continuous software pipeline over sub-tiles ("units": u = kSJ*si + sj).
+// Unit u is 4 slots; slot g issues MFMA g (K = 32 of the 128) of unit u and, in the 32
 // cycles the matrix core needs for it, 8 vector-ALU instructions that fold the finished INT32
 // tile of unit u-1 into the FP32 accumulators: the 4 FMAs of the elements converted one slot
 // earlier, then the 4 converts of elements 4g..4g+3.  An FMA never waits for its convert, and a
 // convert reads an MFMA result that is at least 11 issue slots old, as the hardware requires.
 // Fragment registers are refilled from LDS well before their next use: the A fragments of si+1
 // are fetched into a second register buffer while si is being multiplied (LDS latency under
-// load is several hundred cycles), and units 6 and 7 fetch the B fragments and the first A
-// fragments of the NEXT item, so that no item starts with a burst of LDS reads.  Scheduling
+// load is several hundred cycles), and the last two units fetch the B fragments and the first
+// A fragments of the NEXT item, so that no item starts with a burst of LDS reads.  Scheduling
 // fences pin this order.
-//   a_cur: A pair of the current item in LDS; a_nxt / b_nxt: A pair / B block of the next item.
-//   s0, s1: scales of the current item's two i-blocks; sp: scale of the previous item's si = 3.
-template <int u>
-__device__ __forceinline__ void run_unit(WaveState& st, const int8_t* a_cur, const int8_t* a_nxt,
-                                         const int8_t* b_nxt, int h, int jq, int lane, float s0,
-                                         float s1, float sp) {
-  constexpr int si = u >> 1, sj = u & 1;
+//   a_cur: A set of the current item in LDS; a_nxt / b_nxt: A set / B set of the next item.
+//   sc: scales of the current item; sp: scales of the previous item's last two units.
+//   h, c: this wavefront's row half and column group.
+template <class G, int u>
+__device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, const int8_t* a_nxt,
+                                         const int8_t* b_nxt, int h, int c, int lane,
+                                         const ItemScales<G>& sc, const float (&sp)[G::kSP]) {
+  constexpr int kSJ = G::kSJ, kUnits = G::kUnits;
+  constexpr int si = u / kSJ, sj = u % kSJ;
+  // B fragments of column group cg = kSJ*c + sj of the tile: block cg / 4, row group cg % 4
+  auto b_frag = [&](int j, int g) {
+    const int cg = kSJ * c + j;
+    return lds_frag(b_nxt + (cg >> 2) * kBlockBytes, cg & 3, g, lane);
+  };
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     {
       const v16i z = {0};
       st.P[u & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(st.aq[si & 1][g], st.bq[sj][g],
                                                           g ? st.P[u & 1] : z, 0, 0, 0);
-      // A fragments of the next si (of the next item for si = 3) go into the other aq buffer
-      // a whole unit before their first use
-      if (u < 6 && sj == 0)
+      // A fragments of the next si go into the other aq buffer a whole unit before their
+      // first use
+      if (si + 1 < G::kSI && sj == 0)
         st.aq[(si + 1) & 1][g] =
             lds_frag(a_cur + ((si + 1) >> 1) * kBlockBytes, 2 * h + ((si + 1) & 1), g, lane);
-      if (u == 6) {
+      // the last two units (same si, odd: they use aq[1]) fetch the next item's first fragments;
+      // a bq buffer is refilled right after its last use
+      if (u == kUnits - 2) {
         st.aq[0][g] = lds_frag(a_nxt, 2 * h, g, lane);
-        st.bq[0][g] = lds_frag(b_nxt, 2 * (jq & 1), g, lane);
+        st.bq[sj][g] = b_frag(sj, g);
       }
-      if (u == 7) st.bq[1][g] = lds_frag(b_nxt, 2 * (jq & 1) + 1, g, lane);
+      if (u == kUnits - 1) {
+        st.bq[sj][g] = b_frag(sj, g);
+#pragma unroll
+        for (int j = 0; j + 2 < kSJ; ++j) st.bq[j][g] = b_frag(j, g);
+      }
       pin(st.P[u & 1]);
     }
     __builtin_amdgcn_sched_barrier(0);   // MFMA first: its destination must not alias live tiles
     {
       // FMAs of the 4 elements converted in the previous slot (unit u-1, or u-2 for g = 0);
-      // negative units are units 6, 7 of the previous item (si = 3)
+      // negative units are the last two units of the previous item
+      constexpr int kLastSi = G::kSI - 1;
       const int fu = g ? u - 1 : u - 2, fc = g ? g - 1 : 3;
-      const int fsi = fu < 0 ? 3 : (fu >> 1), fsj = fu & 1;
-      const float s = fu < 0 ? sp : (fsi < 2 ? s0 : s1);
+      const bool prev = fu < 0;
+      const int pu = fu + kUnits;                       // unit index in the previous item
+      const int fsi = prev ? kLastSi : fu / kSJ, fsj = prev ? pu % kSJ : fu % kSJ;
+      const float s = prev ? sp[G::kSP == 1 ? 0 : pu - (kUnits - 2)]
+                           : sc.s[fsi >> 1][G::kSC == 1 ? 0 : fsj];
 #pragma unroll
       for (int i = 0; i < 4; ++i)
         st.acc[fsi][fsj][4 * fc + i] = __builtin_fmaf(st.T[i], s, st.acc[fsi][fsj][4 * fc + i]);
@@ -159,73 +212,86 @@ __device__ __forceinline__ void run_unit(WaveState& st, const int8_t* a_cur, con
   }
 }
 
-// Folds the last unit (si = 3, sj = 1) of the last item into the accumulators.
-__device__ __forceinline__ void drain(WaveState& st, float s1) {
-#pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    const int fsj = g ? 1 : 0, fc = g ? g - 1 : 3;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      st.acc[3][fsj][4 * fc + i] = __builtin_fmaf(st.T[i], s1, st.acc[3][fsj][4 * fc + i]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) st.T[i] = (float)st.P[1][4 * g + i];
+// Units [kFrom, kTo) of one item, in order.
+template <class G, int kFrom, int kTo>
+__device__ __forceinline__ void run_units_range(WaveState<G>& st, const int8_t* a_cur,
+                                                const int8_t* a_nxt, const int8_t* b_nxt, int h,
+                                                int c, int lane, const ItemScales<G>& sc,
+                                                const float (&sp)[G::kSP]) {
+  if constexpr (kFrom < kTo) {
+    run_unit<G, kFrom>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
+    run_units_range<G, kFrom + 1, kTo>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
   }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) st.acc[3][1][12 + i] = __builtin_fmaf(st.T[i], s1, st.acc[3][1][12 + i]);
 }
 
-// Scalars of one k-block: residual slots and scales of the tile's two A blocks, scale of this
-// wave's B block.
+// Folds the last two units of the last item (scales sp) into the accumulators.
+template <class G>
+__device__ __forceinline__ void drain(WaveState<G>& st, const float (&sp)[G::kSP]) {
+  constexpr int kLastSi = G::kSI - 1, kSJ = G::kSJ;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const int fsj = g ? kSJ - 1 : kSJ - 2, fc = g ? g - 1 : 3;
+    const float s = sp[G::kSP == 1 ? 0 : (g ? 1 : 0)];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      st.acc[kLastSi][fsj][4 * fc + i] = __builtin_fmaf(st.T[i], s, st.acc[kLastSi][fsj][4 * fc + i]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) st.T[i] = (float)st.P[(G::kUnits - 1) & 1][4 * g + i];
+  }
+  const float s = sp[G::kSP - 1];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    st.acc[kLastSi][kSJ - 1][12 + i] = __builtin_fmaf(st.T[i], s, st.acc[kLastSi][kSJ - 1][12 + i]);
+}
+
+// Scalars of one k-block: residual slots and scales of the tile's A blocks, scales of the (up
+// to two) B blocks this wave's columns lie in.
+template <class G>
 struct KRec {
-  int slot0, slot1;
-  float sa0, sa1, sb;
-  float rs0, rs1;   // residual scales of the two A blocks (valid where the slot is >= 0)
+  int slot[G::kBI];
+  float sa[G::kBI];
+  float rs[G::kBI];   // residual scales (valid where the slot is >= 0)
+  float sb[2];
 };
 
 }  // namespace
 
-__global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
-  extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
-  int8_t* const a_ring = lds;                   // [2][2 blocks]
-  int8_t* const b_ring = lds + 2 * kRingBytes;  // [2][2 blocks]
-  constexpr bool kDebug = false;
+namespace {
+
+// One output tile of geometry G whose first blocks are (ib_first, jb_first).  Blocks beyond
+// the matrix repeat the last valid one (their products are never stored).
+template <class G>
+__device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int jb_first,
+                                          int8_t* lds) {
+  constexpr int kBI = G::kBI, kBJ = G::kBJ, kSI = G::kSI, kSJ = G::kSJ, kUnits = G::kUnits;
+  int8_t* const a_ring = lds;                    // [2][kBI blocks]
+  int8_t* const b_ring = lds + 2 * G::kASet;     // [2][kBJ blocks]
 
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int h = w >> 2, jq = w & 3;
+  const int h = w >> 2, c = w & 3;
 
-  // ---- tile of this workgroup; out-of-range blocks repeat the last valid one (never stored).
-  // Workgroups are dealt to the 8 XCDs round-robin by id, and each XCD has its own L2.  Remap
-  // ids so that one XCD works through a contiguous run of tiles, and order the tiles in groups
-  // of kGroupN tile-columns walked row by row: the ~32 tiles resident on an XCD then form an
-  // 8 x 4 patch that shares its A and B blocks through that L2.  Grouping by columns (not rows)
-  // gives every XCD tiles from all tile-rows, so fallback blocks clustered in a few block-rows
-  // (the worst case of Sec. 6.3) load the XCDs evenly.
-  const int tiles_i = (p.nib + 1) >> 1, tiles_j = (p.njb + 1) >> 1;
-  int ti, tj;
-  {
-    const int total = tiles_i * tiles_j;
-    const int b = blockIdx.x, xcd = b % kXcds, l = b / kXcds;
-    const int q = total / kXcds, rem = total % kXcds;
-    const int L = xcd * q + min(xcd, rem) + l;
-    const int group = kGroupN * tiles_i;
-    const int g0 = (L / group) * kGroupN;
-    const int gn = min(kGroupN, tiles_j - g0);
-    const int within = L - (L / group) * group;
-    tj = g0 + within % gn;
-    ti = within / gn;
-  }
-  const int ib0 = ti * 2, ib1 = min(ti * 2 + 1, p.nib - 1);
-  const int jb0 = tj * 2, jb1 = min(tj * 2 + 1, p.njb - 1);
-  const int jb = (jq >> 1) ? jb1 : jb0;   // the j-block this wave multiplies with
+  int ib[kBI], jbt[kBJ];
+#pragma unroll
+  for (int i = 0; i < kBI; ++i) ib[i] = min(ib_first + i, p.nib - 1);
+#pragma unroll
+  for (int j = 0; j < kBJ; ++j) jbt[j] = min(jb_first + j, p.njb - 1);
+  // the (up to two) j-blocks this wave's columns lie in, as indices into the tile's blocks
+  const int jlo = (kSJ * c) >> 2, jhi = (kSJ * c + kSJ - 1) >> 2;
 
-  // ---- what this wave stages: waves 0-3 the A pair, waves 4-7 the B pair, 8 KiB each
-  const bool stage_a = w < 4;
-  const int shalf = (w >> 1) & 1;            // which block of the pair
-  const int sblk = shalf ? (stage_a ? ib1 : jb1) : (stage_a ? ib0 : jb0);
-  const int soff = shalf * kBlockBytes + (w & 1) * (kBlockBytes / 2);
+  // ---- what this wave stages: 8 KiB (half a block) per item; the first 2*kBI waves the A
+  // blocks, the others the B blocks
+  const bool stage_a = w < 2 * kBI;
+  const int sidx = stage_a ? (w >> 1) : ((w - 2 * kBI) >> 1);   // which block of the set
+  const int spart = (w & 1) * (kBlockBytes / 2);
+  int sblk = 0;
+#pragma unroll
+  for (int i = 0; i < kBI; ++i) if (stage_a && sidx == i) sblk = ib[i];
+#pragma unroll
+  for (int j = 0; j < kBJ; ++j) if (!stage_a && sidx == j) sblk = jbt[j];
+  const int soff = sidx * kBlockBytes + spart;
   const int8_t* const smain = (stage_a ? p.a_codes : p.b_codes) +
-                              (int64_t)sblk * p.nkb * kBlockBytes + (w & 1) * (kBlockBytes / 2);
+                              (int64_t)sblk * p.nkb * kBlockBytes + spart;
 
   // Scales and slots are read-only for the whole kernel: reading them through the constant
   // address space makes them scalar loads, which do not share a counter with the vector loads.
@@ -236,65 +302,86 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
   cfloat* const r_sc = (cfloat*)p.a_res_scales;
   cint* const a_sl = (cint*)p.a_slot;
   const bool has_fb = p.a_slot != nullptr;
-  const int ia0 = ib0 * p.a_si, ia1 = ib1 * p.a_si, ibj = jb * p.b_sj;
+  int ia[kBI];
+#pragma unroll
+  for (int i = 0; i < kBI; ++i) ia[i] = ib[i] * p.a_si;
+  int jlo_blk = jbt[0], jhi_blk = jbt[0];
+#pragma unroll
+  for (int j = 0; j < kBJ; ++j) {
+    if (jlo == j) jlo_blk = jbt[j];
+    if (jhi == j) jhi_blk = jbt[j];
+  }
+  const int ibj_lo = jlo_blk * p.b_sj, ibj_hi = jhi_blk * p.b_sj;
   const int nkb = p.nkb;
 
-  auto load_rec = [&](int k) -> KRec {
-    KRec r{-1, -1, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+  auto load_rec = [&](int k) -> KRec<G> {
+    KRec<G> r;
+#pragma unroll
+    for (int i = 0; i < kBI; ++i) { r.slot[i] = -1; r.sa[i] = 0.0f; r.rs[i] = 0.0f; }
+    r.sb[0] = r.sb[1] = 0.0f;
     if (k < nkb) {
-      if (has_fb) {
-        r.slot0 = a_sl[ia0 + k * p.a_sk];
-        r.slot1 = a_sl[ia1 + k * p.a_sk];
+#pragma unroll
+      for (int i = 0; i < kBI; ++i) {
+        if (has_fb) r.slot[i] = a_sl[ia[i] + k * p.a_sk];
+        r.sa[i] = a_sc[ia[i] + k * p.a_sk];
       }
-      r.sa0 = a_sc[ia0 + k * p.a_sk];
-      r.sa1 = a_sc[ia1 + k * p.a_sk];
-      r.sb = b_sc[ibj + k * p.b_sk];
+      r.sb[0] = b_sc[ibj_lo + k * p.b_sk];
+      if (G::kSC > 1) r.sb[1] = b_sc[ibj_hi + k * p.b_sk];
     }
     return r;
   };
   // Residual scales depend on the slots, so they are fetched one step after the record itself:
   // by then the slots have arrived and the dependent load does not stall the wavefront.
-  auto load_res_scales = [&](KRec& r) {
-    if (r.slot0 >= 0) r.rs0 = r_sc[r.slot0];
-    if (r.slot1 >= 0) r.rs1 = r_sc[r.slot1];
+  auto load_res_scales = [&](KRec<G>& r) {
+#pragma unroll
+    for (int i = 0; i < kBI; ++i) if (r.slot[i] >= 0) r.rs[i] = r_sc[r.slot[i]];
+  };
+  auto any_flagged = [&](const KRec<G>& r) {
+    bool f = false;
+#pragma unroll
+    for (int i = 0; i < kBI; ++i) f |= r.slot[i] >= 0;
+    return f;
   };
   // Stages this wave's 8 KiB share of item (k, res) into ring slot `asel` (A) / k & 1 (B).
-  auto stage_item = [&](int k, int res, const KRec& r, int asel, bool new_b) {
+  auto stage_item = [&](int k, int res, const KRec<G>& r, int asel, bool new_b) {
     if (stage_a) {
       const int8_t* src;
       if (res) {
-        const int s = shalf ? r.slot1 : r.slot0;
-        if (s < 0) return;   // unflagged half: nothing to bring (its scale will be zero)
-        src = p.a_res + (int64_t)s * kBlockBytes + (w & 1) * (kBlockBytes / 2);
+        int s = -1;
+#pragma unroll
+        for (int i = 0; i < kBI; ++i) if (sidx == i) s = r.slot[i];
+        if (s < 0) return;   // unflagged block: nothing to bring (its scale will be zero)
+        src = p.a_res + (int64_t)s * kBlockBytes + spart;
       } else {
         src = smain + (int64_t)k * kBlockBytes;
       }
-      stage_half_block(src, a_ring + asel * kRingBytes + soff, lane);
+      stage_half_block(src, a_ring + asel * G::kASet + soff, lane);
     } else if (new_b) {
-      stage_half_block(smain + (int64_t)k * kBlockBytes, b_ring + (k & 1) * kRingBytes + soff, lane);
+      stage_half_block(smain + (int64_t)k * kBlockBytes, b_ring + (k & 1) * G::kBSet + soff, lane);
     }
   };
+  // scale column sc belongs to the wave's second j-block?
+  auto sc_is_hi = [&](int scol) { return ((kSJ * c + scol) >> 2) != jlo; };
 
-  WaveState st;
-  float (&acc)[4][2][16] = st.acc;
+  WaveState<G> st;
 #pragma unroll
-  for (int si = 0; si < 4; ++si)
+  for (int si = 0; si < kSI; ++si)
 #pragma unroll
-    for (int sj = 0; sj < 2; ++sj)
+    for (int sj = 0; sj < kSJ; ++sj)
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.acc[si][sj][r] = 0.0f;
-  bool poison0 = false, poison1 = false;
-  if (nkb <= 0) goto store;   // empty contraction: all zeros
+  bool poison[kBI];
+#pragma unroll
+  for (int i = 0; i < kBI; ++i) poison[i] = false;
 
-  {
+  if (nkb > 0) {
     // ---- prologue: items 0 and 1 into the two ring slots
     // records are fetched two k-blocks ahead so that no scalar load is waited for in the loop
-    KRec r0 = load_rec(0), r1 = load_rec(1), r2 = load_rec(2);
+    KRec<G> r0 = load_rec(0), r1 = load_rec(1), r2 = load_rec(2);
     int k = 0, res = 0, t = 0;
     stage_item(0, 0, r0, 0, true);
     {
-      const bool n1res = r0.slot0 >= 0 || r0.slot1 >= 0;
-      if (n1res) stage_item(0, 1, r0, 1, false);
+      if (any_flagged(r0)) stage_item(0, 1, r0, 1, false);
       else if (1 < nkb) stage_item(1, 0, r1, 1, true);
     }
     load_res_scales(r0);
@@ -304,49 +391,53 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       st.aq[0][g] = lds_frag(a_ring, 2 * h, g, lane);
-      st.bq[0][g] = lds_frag(b_ring + (jq >> 1) * kBlockBytes, 2 * (jq & 1), g, lane);
-      st.bq[1][g] = lds_frag(b_ring + (jq >> 1) * kBlockBytes, 2 * (jq & 1) + 1, g, lane);
+#pragma unroll
+      for (int j = 0; j < kSJ; ++j) {
+        const int cg = kSJ * c + j;
+        st.bq[j][g] = lds_frag(b_ring + (cg >> 2) * kBlockBytes, cg & 3, g, lane);
+      }
     }
     st.P[1] = v16i{0};
 #pragma unroll
     for (int i = 0; i < 4; ++i) st.T[i] = 0.0f;
-    float sp = 0.0f;                       // scale of the previous item's second i-block
+    float sp[G::kSP];                      // scales of the previous item's last two units
+#pragma unroll
+    for (int i = 0; i < G::kSP; ++i) sp[i] = 0.0f;
 
     for (;;) {
       // ---- the items after this one (all wave-uniform scalar logic)
-      const bool n1res = !res && (r0.slot0 >= 0 || r0.slot1 >= 0);
+      const bool n1res = !res && any_flagged(r0);
       const int n1k = n1res ? k : k + 1;
       const bool has1 = n1k < nkb;
-      const bool n2res = !n1res && (r1.slot0 >= 0 || r1.slot1 >= 0);
+      const bool n2res = !n1res && any_flagged(r1);
       const int n2k = (n1res || n2res) ? k + 1 : k + 2;
       const bool has2 = n2k < nkb;
 
       // ---- scales of this item
-      float s0, s1;
-      if (!res) {
-        s0 = r0.sa0 * r0.sb;
-        s1 = r0.sa1 * r0.sb;
-        poison0 |= r0.slot0 == -2;
-        poison1 |= r0.slot1 == -2;
-      } else {   // an unflagged half multiplies stale LDS contents by zero: adds +0
-        s0 = r0.slot0 >= 0 ? r0.rs0 * r0.sb : 0.0f;
-        s1 = r0.slot1 >= 0 ? r0.rs1 * r0.sb : 0.0f;
+      ItemScales<G> sc;
+#pragma unroll
+      for (int i = 0; i < kBI; ++i) {
+        float sa;
+        if (!res) {
+          sa = r0.sa[i];
+          poison[i] |= r0.slot[i] == -2;
+        } else {   // an unflagged block multiplies stale LDS contents by zero: adds +0
+          sa = r0.slot[i] >= 0 ? r0.rs[i] : 0.0f;
+        }
+#pragma unroll
+        for (int q = 0; q < G::kSC; ++q)
+          sc.s[i][q] = sa * ((G::kSC > 1 && sc_is_hi(q)) ? r0.sb[1] : r0.sb[0]);
       }
 
-      const int8_t* const a_cur = a_ring + (t & 1) * kRingBytes;
-      const int8_t* const a_nxt = a_ring + ((t + 1) & 1) * kRingBytes;
-      const int8_t* const b_nxt = b_ring + (n1k & 1) * kRingBytes + (jq >> 1) * kBlockBytes;
+      const int8_t* const a_cur = a_ring + (t & 1) * G::kASet;
+      const int8_t* const a_nxt = a_ring + ((t + 1) & 1) * G::kASet;
+      const int8_t* const b_nxt = b_ring + (n1k & 1) * G::kBSet;
 
-      run_unit<0>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
-      run_unit<1>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
-      run_unit<2>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
-      run_unit<3>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
-      run_unit<4>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
-      run_unit<5>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
+      run_units_range<G, 0, kUnits - 2>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
 
-      // All LDS reads of this item are issued (units 6, 7 run from registers).  Wait for them
-      // and for the next item's direct-to-LDS loads, then the barrier publishes the next item
-      // and frees this item's ring slots for the item after it.
+      // All LDS reads of this item are issued (the last two units run from registers).  Wait
+      // for them and for the next item's direct-to-LDS loads, then the barrier publishes the
+      // next item and frees this item's ring slots for the item after it.
       __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
       __syncthreads();
       if (has2) {
@@ -354,10 +445,11 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
         else stage_item(n2k, 0, r1, t & 1, n2k != n1k);
       }
 
-      run_unit<6>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
-      run_unit<7>(st, a_cur, a_nxt, b_nxt, h, jq, lane, s0, s1, sp);
+      run_units_range<G, kUnits - 2, kUnits>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
 
-      sp = s1;
+#pragma unroll
+      for (int i = 0; i < G::kSP; ++i)
+        sp[i] = sc.s[kBI - 1][G::kSC == 1 ? 0 : kSJ - 2 + i];
       if (!has1) break;
       // ---- advance to the next item
       ++t;
@@ -372,42 +464,39 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
         r2 = load_rec(k + 2);
       }
     }
-    drain(st, sp);
+    drain<G>(st, sp);
   }
-store:
+
   // ---- epilogue.  The MFMA result layout (lane = column, registers = rows) would give 64-byte
   // global stores; instead each wavefront transposes its tile through a private LDS patch
-  // (64 rows x 64 columns of FP32 at a time, row pitch 72 floats: conflict-free both ways) and
-  // writes whole 128/256-byte row segments with 16-byte stores.
+  // (32 rows x 32*kSJ columns of FP32 at a time, row pitch + 8 floats: conflict-free both
+  // ways) and writes whole row segments with 16-byte stores.
   __syncthreads();   // every wavefront is done reading the operand rings
-  if (tj * 2 + (jq >> 1) >= p.njb) return;
-  float* const stg = reinterpret_cast<float*>(lds + w * kStageBytesPerWave);
-  const int col0 = jb * kBlock + (jq & 1) * 64;        // first column of this wave's tile
+  float* const stg = reinterpret_cast<float*>(lds + w * G::kStageBytesPerWave);
+  const int col0 = jb_first * kBlock + c * G::kStageCols;   // first column of this wave's tile
 #pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    if (half && ti * 2 + 1 >= p.nib) break;
-    const bool poison = !kDebug && (half ? poison1 : poison0);
+  for (int si = 0; si < kSI; ++si) {
     // a flagged block whose residual found no slot cannot be computed: poison its rows
+    const bool bad = poison[si >> 1];
 #pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2)
+    for (int sj = 0; sj < kSJ; ++sj)
 #pragma unroll
-      for (int sj = 0; sj < 2; ++sj)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int rl = s2 * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          const int cl = sj * 32 + (lane & 31);
-          stg[rl * kStagePitch + cl] = poison ? __int_as_float(0x7FC00000) : acc[half * 2 + s2][sj][r];
-        }
-    const int row0 = (half ? ib1 : ib0) * kBlock + h * 64;
-    if (!kDebug && p.out_bf16) {
+      for (int r = 0; r < 16; ++r) {
+        const int rl = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int cl = sj * 32 + (lane & 31);
+        stg[rl * G::kStagePitch + cl] = bad ? __int_as_float(0x7FC00000) : st.acc[si][sj][r];
+      }
+    const int row0 = (ib_first + (si >> 1)) * kBlock + h * 64 + (si & 1) * 32;
+    if (p.out_bf16) {
       uint16_t* const C = reinterpret_cast<uint16_t*>(p.c);
-      const int c8 = (lane & 7) * 8;
+      constexpr int kChunks = G::kStageCols / 8;         // 16-byte chunks per row
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int rl = it * 8 + (lane >> 3);
+      for (int it = 0; it < 32 * kChunks / 64; ++it) {
+        const int idx = it * 64 + lane;
+        const int rl = idx / kChunks, c8 = (idx % kChunks) * 8;
         const int row = row0 + rl, col = col0 + c8;
-        const float4 lo = *reinterpret_cast<const float4*>(stg + rl * kStagePitch + c8);
-        const float4 hi = *reinterpret_cast<const float4*>(stg + rl * kStagePitch + c8 + 4);
+        const float4 lo = *reinterpret_cast<const float4*>(stg + rl * G::kStagePitch + c8);
+        const float4 hi = *reinterpret_cast<const float4*>(stg + rl * G::kStagePitch + c8 + 4);
         if (row >= p.M || col >= p.N) continue;
         uint16_t* dst = C + (int64_t)row * p.ldc + col;
         if (p.vec_ok && col + 8 <= p.N) {
@@ -424,12 +513,13 @@ store:
       }
     } else {
       float* const C = reinterpret_cast<float*>(p.c);
-      const int c4 = (lane & 15) * 4;
+      constexpr int kChunks = G::kStageCols / 4;
 #pragma unroll
-      for (int it = 0; it < 16; ++it) {
-        const int rl = it * 4 + (lane >> 4);
+      for (int it = 0; it < 32 * kChunks / 64; ++it) {
+        const int idx = it * 64 + lane;
+        const int rl = idx / kChunks, c4 = (idx % kChunks) * 4;
         const int row = row0 + rl, col = col0 + c4;
-        const float4 v = *reinterpret_cast<const float4*>(stg + rl * kStagePitch + c4);
+        const float4 v = *reinterpret_cast<const float4*>(stg + rl * G::kStagePitch + c4);
         if (row >= p.M || col >= p.N) continue;
         float* dst = C + (int64_t)row * p.ldc + col;
         if (p.vec_ok && col + 4 <= p.N) {
@@ -442,6 +532,41 @@ store:
         }
       }
     }
+  }
+}
+
+// Workgroups are dealt to the 8 XCDs round-robin by id, and each XCD has its own L2.  Remap ids
+// so that one XCD works through a contiguous run of tiles, and order the tiles in groups of
+// kGroupN tile-columns walked row by row: the ~32 tiles resident on an XCD then form a patch
+// that shares its A and B blocks through that L2.  Grouping by columns (not rows) gives every
+// XCD tiles from all tile-rows, so fallback blocks clustered in a few block-rows (the worst
+// case of Sec. 6.3) load the XCDs evenly.  b in [0, tiles_i * tiles_j) -> (ti, tj), a bijection.
+__device__ __forceinline__ void tile_of(int b, int tiles_i, int tiles_j, int& ti, int& tj) {
+  const int total = tiles_i * tiles_j;
+  const int xcd = b % kXcds, l = b / kXcds;
+  const int q = total / kXcds, rem = total % kXcds;
+  const int L = xcd * q + min(xcd, rem) + l;
+  const int group = kGroupN * tiles_i;
+  const int g0 = (L / group) * kGroupN;
+  const int gn = min(kGroupN, tiles_j - g0);
+  const int within = L - (L / group) * group;
+  tj = g0 + within % gn;
+  ti = within / gn;
+}
+
+}  // namespace
+
+// Grid: p.n_main workgroups compute 2 x 2-block tiles covering block columns [0, 2*main_tj),
+// the rest 1 x 3-block tiles covering block columns [2*main_tj, njb).
+__global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
+  int ti, tj;
+  if ((int)blockIdx.x < p.n_main) {
+    tile_of(blockIdx.x, (p.nib + 1) >> 1, p.main_tj, ti, tj);
+    tile_body<Geo<2, 2>>(p, 2 * ti, 2 * tj, lds);
+  } else {
+    tile_of(blockIdx.x - p.n_main, p.nib, p.tail_tj, ti, tj);
+    tile_body<Geo<1, 3>>(p, ti, 2 * p.main_tj + 3 * tj, lds);
   }
 }
 
@@ -481,14 +606,77 @@ __global__ __launch_bounds__(256) void partials_kernel(GemmParams p) {
   }
 }
 
-hipError_t launch_gemm(const GemmParams& p, bool debug, hipStream_t st) {
+namespace {
+
+struct TilePlan {
+  int n_main;    // workgroups computing 2 x 2-block tiles
+  int main_tj;   // tile columns they cover (block columns [0, 2*main_tj))
+  int tail_tj;   // 1 x 3-block tile columns covering the remaining block columns
+};
+
+// All of the output in 2 x 2-block tiles, unless their number leaves the last round of the
+// chip mostly idle: then the last block columns are cut into 1 x 3-block tiles (3/4 of the work
+// of a 2 x 2 tile each) so that the final round is shorter.  Costs are in units of one 2 x 2
+// tile per compute unit.
+TilePlan plan_tiles(int nib, int njb, int cus) {
+  const int tiles_i = (nib + 1) / 2, tiles_j = (njb + 1) / 2;
+  const int total = tiles_i * tiles_j;
+  const TilePlan all{total, tiles_j, 0};
+  if (cus <= 0 || total <= cus || total % cus == 0) return all;
+  const int rounds = total / cus;
+  const int cm = std::min(tiles_j, rounds * cus / tiles_i);
+  const int tail_cols = njb - 2 * cm;
+  if (cm <= 0 || tail_cols <= 0) return all;
+  const int tail_tj = (tail_cols + 2) / 3;
+  const int n_tail = nib * tail_tj;
+  const double cost_all = (total + cus - 1) / cus;
+  const double cost_split = (cm * tiles_i + cus - 1) / cus + 0.75 * ((n_tail + cus - 1) / cus);
+  if (cost_split + 0.05 < cost_all) return TilePlan{cm * tiles_i, cm, tail_tj};
+  return all;
+}
+
+// Compute units the planner assumes: the device's, or the value of the environment variable
+// FQ_GEMM_CUS when it is set to a positive number (tuning and tests: a small value makes small
+// problems take the mixed-geometry path).
+int planning_cus() {
+  if (const char* e = std::getenv("FQ_GEMM_CUS")) {
+    const int v = std::atoi(e);
+    if (v > 0) return v;
+  }
+  static int cached = 0;
+  if (cached == 0) {
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+      cached = prop.multiProcessorCount;
+    else
+      cached = -1;
+  }
+  return cached;
+}
+
+}  // namespace
+
+void gemm_tile_plan(int nib, int njb, int cus, int out[3]) {
+  const TilePlan plan = plan_tiles(nib, njb, cus > 0 ? cus : planning_cus());
+  out[0] = plan.n_main;
+  out[1] = plan.main_tj;
+  out[2] = plan.tail_tj;
+}
+
+hipError_t launch_gemm(const GemmParams& p_in, bool debug, hipStream_t st) {
   if (debug) {
-    if (p.nib * p.njb == 0) return hipSuccess;
-    hipLaunchKernelGGL(partials_kernel, dim3(p.nib * p.njb), dim3(256), 0, st, p);
+    if (p_in.nib * p_in.njb == 0) return hipSuccess;
+    hipLaunchKernelGGL(partials_kernel, dim3(p_in.nib * p_in.njb), dim3(256), 0, st, p_in);
     return hipGetLastError();
   }
-  const int tiles = ((p.nib + 1) / 2) * ((p.njb + 1) / 2);
-  if (tiles == 0) return hipSuccess;
+  if (p_in.nib == 0 || p_in.njb == 0) return hipSuccess;
+  GemmParams p = p_in;
+  const TilePlan plan = plan_tiles(p.nib, p.njb, planning_cus());
+  p.n_main = plan.n_main;
+  p.main_tj = plan.main_tj;
+  p.tail_tj = plan.tail_tj;
+  const int grid = plan.n_main + p.nib * plan.tail_tj;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel),
@@ -496,7 +684,7 @@ hipError_t launch_gemm(const GemmParams& p, bool debug, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(gemm_kernel, dim3(tiles), dim3(kThreads), kLdsBytes, st, p);
+  hipLaunchKernelGGL(gemm_kernel, dim3(grid), dim3(kThreads), kLdsBytes, st, p);
   return hipGetLastError();
 }
 

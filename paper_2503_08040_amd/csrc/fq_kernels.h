@@ -50,6 +50,7 @@ struct GemmParams {
   int nib, njb, nkb;
   int out_bf16;
   int vec_ok;                 // C base and row pitch allow 16-byte stores
+  int n_main, main_tj, tail_tj;   // tile plan, filled in by launch_gemm
   int debug_k;                // debug mode: the single k-block to evaluate
   int debug_residual;         // debug mode: 0 main term, 1 residual term
 };
@@ -73,6 +74,9 @@ struct CtxParams {
 hipError_t launch_quantize(const QuantParams& p, hipStream_t st);
 hipError_t launch_untile(const int8_t* tiled, int rows, int cols, int8_t* dense, hipStream_t st);
 hipError_t launch_gemm(const GemmParams& p, bool debug, hipStream_t st);
+// out = {workgroups with 2x2-block tiles, tile columns they cover, 1x3-block tile columns};
+// cus <= 0: the current device's compute units (or FQ_GEMM_CUS).
+void gemm_tile_plan(int nib, int njb, int cus, int out[3]);
 hipError_t launch_ctx(const CtxParams& p, bool dequantize, hipStream_t st);
 
 }  // namespace fq

@@ -108,6 +108,36 @@ def test_ragged_and_multi_tile_shapes(op, sa, sb):
     _check_gemm(op, ga, gb, oa, ob, f"ragged op={op} {sa}x{sb}", partials=(sa[0] <= 300))
 
 
+@pytest.mark.parametrize("op,sa,sb,cus", [
+    (fq.FQ_OP_NT, (700, 300), (1100, 300), 6),     # 128x384 tiles with one valid block column
+    (fq.FQ_OP_NT, (700, 300), (1100, 300), 10),    # three valid block columns
+    (fq.FQ_OP_NT, (300, 260), (1300, 260), 7),     # two columns of 128x384 tiles, the last ragged
+    (fq.FQ_OP_NN, (300, 200), (200, 1300), 7),
+    (fq.FQ_OP_TN, (200, 700), (200, 1100), 10),
+    (fq.FQ_OP_NT, (129, 128), (1281, 128), 5),     # one k-block, ragged rows and columns
+])
+def test_mixed_tile_geometries(op, sa, sb, cus, monkeypatch):
+    """The planner's second geometry (128 x 384 tiles for the last block columns), forced on
+    small problems by telling the planner the GPU has only a few compute units."""
+    monkeypatch.setenv("FQ_GEMM_CUS", str(cus))
+    rng = np.random.default_rng(sa[0] + 3 * sb[1] + op + cus)
+    a = rng.standard_normal(sa).astype(F32)
+    for _ in range(12):
+        a[rng.integers(sa[0]), rng.integers(sa[1])] *= 120.0
+    b = rng.standard_normal(sb).astype(F32) * F32(0.02)
+    ga, gb, oa, ob = _quant_pair(synth.to_bf16_bits(a), synth.to_bf16_bits(b),
+                                 fq.FQ_CRIT_ABSMAX_GT, 8.0)
+    Mo, No = fqo.out_shape(op, oa, ob)
+    plan = fq.fq_gemm_tile_plan(Mo, No)
+    assert plan[2] > 0 and plan[0] > 0, f"plan {plan} does not use both geometries"
+    assert int(oa.fb_count[0]) > 0
+    c = _check_gemm(op, ga, gb, oa, ob, f"mixed op={op} {sa}x{sb} cus={cus} plan={plan}", partials=False)
+    # the plan does not change a single bit of the result
+    monkeypatch.setenv("FQ_GEMM_CUS", "1000000")
+    assert fq.fq_gemm_tile_plan(Mo, No)[2] == 0
+    assert np.array_equal(fq.fq_gemm(op, ga, gb).cpu().numpy(), c)
+
+
 def test_strided_output_and_reuse():
     wl = synth.config1()
     ga, gb, oa, ob = _quant_pair(wl.X, wl.W, fq.FQ_CRIT_ABSMAX_GT, wl.theta)
@@ -163,7 +193,7 @@ def _sampled_windows(rng, Mo, No, flagged_rows, n=24, h=4, w=8):
 
 
 @pytest.mark.parametrize("cfg", ["cfg2", "cfg3", "cfg5_random", "cfg5_sequential"])
-def test_full_size_sampled(cfg):
+def test_full_size_sampled(cfg, monkeypatch):
     """BASELINE configs 2, 3 and 5 at full size, in the launch configuration the
     benchmark times: quantizer outputs bit-exact in full, GEMM outputs compared
     on sampled windows the oracle computes element by element (windows cover
@@ -196,6 +226,14 @@ def test_full_size_sampled(cfg):
         gotb = c[i0:i1, j0:j1].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
         assert np.array_equal(gotb, refb[i0:i1, j0:j1])
     assert worst <= TOL
-    # properties that hold at any size: finite everywhere, bf16 output is the rounding of fp32
+    # properties that hold at any size: finite everywhere, bf16 output is the rounding of fp32,
+    # and the result does not depend on the tile plan (config 2 on 256 compute units uses both
+    # tile geometries; forcing a single geometry must give the same bits)
     assert torch.isfinite(c32).all().item()
     assert torch.equal(c, c32.to(torch.bfloat16))
+    plan = fq.fq_gemm_tile_plan(wl.M, wl.N)
+    print(f"{cfg}: tile plan {plan}", flush=True)
+    monkeypatch.setenv("FQ_GEMM_CUS", "1000000")
+    assert fq.fq_gemm_tile_plan(wl.M, wl.N)[2] == 0
+    gu.announce(f"{cfg}: gemm with a single tile geometry")
+    assert torch.equal(fq.fq_gemm(fq.FQ_OP_NT, ga, gb), c32)
