@@ -455,6 +455,71 @@ int fqo_ctx_dequantize(const uint8_t *packed, const float *scales, int rows, int
   return 0;
 }
 
+/*
+ * Gated linear unit y = sigma(x1) * x2 with sigma = SiLU, sigma(x) = x / (1 + e^-x) (Sec. 4.1),
+ * as a non-linear layer of Sec. 5.2: bf16 inputs and output; what it keeps for the backward
+ * pass are the INT10 1 x 128 contexts of x1 and x2 (fqo_ctx_quantize), which the backward pass
+ * dequantizes (Sec. 5.3).  The function values are evaluated in binary64 and rounded once to
+ * bf16.
+ */
+static uint16_t f64_to_bf16_rne(double v) {
+  /* a double rounded once to bf16 (8 significant bits, ties to even; below 2^-126 the spacing
+   * is 2^-133); finite inputs.  rint() uses the default rounding mode: ties to even. */
+  if (v == 0.0) return signbit(v) ? 0x8000u : 0u;
+  int e;
+  (void)frexp(fabs(v), &e);                        /* |v| = m * 2^e, 0.5 <= m < 1 */
+  int quantum = e - 8 < -133 ? -133 : e - 8;       /* exponent of the bf16 spacing at |v| */
+  double r = ldexp(rint(ldexp(fabs(v), -quantum)), quantum);
+  return f32_to_bf16_rne((float)copysign(r, v));   /* r is a bf16 value: both conversions exact */
+}
+
+int fqo_glu_forward(const uint16_t *x1_bf16, const uint16_t *x2_bf16, int rows, int cols,
+                    long ld, uint16_t *y_bf16, long ldy) {
+  if (!x1_bf16 || !x2_bf16 || !y_bf16) return -1;
+  if (rows < 0 || cols < 0 || ld < cols || ldy < cols) return -2;
+  for (int r = 0; r < rows; ++r)
+    for (int c = 0; c < cols; ++c) {
+      double x1 = (double)bf16_to_f32(x1_bf16[(size_t)r * ld + c]);
+      double x2 = (double)bf16_to_f32(x2_bf16[(size_t)r * ld + c]);
+      double silu = x1 / (1.0 + exp(-x1));
+      y_bf16[(size_t)r * ldy + c] = f64_to_bf16_rne(silu * x2);
+    }
+  return 0;
+}
+
+/* Value of element (r, c) of an INT10 context: scale * code, one binary32 multiplication. */
+static float ctx_value(const uint8_t *packed, const float *scales, int ng, int r, int c) {
+  const int G = 128, j = c / G, pos = (c - j * G) * 10;
+  const uint8_t *src = packed + ((size_t)r * ng + j) * 160;
+  uint32_t bits = 0;
+  for (int b = 0; b < 10; ++b)
+    if (src[(pos + b) >> 3] & (1u << ((pos + b) & 7))) bits |= 1u << b;
+  int q = (bits & 0x200u) ? (int)bits - 1024 : (int)bits;
+  return scales[(size_t)r * ng + j] * (float)q;
+}
+
+/* dx2 = dy * silu(x1~), dx1 = dy * x2~ * silu'(x1~), silu'(x) = s (1 + x (1 - s)), s = 1/(1+e^-x),
+ * with x1~, x2~ the dequantized contexts; binary64 evaluation, one rounding to bf16. */
+int fqo_glu_backward(const uint16_t *dy_bf16, long ld_dy, const uint8_t *packed1,
+                     const float *scales1, const uint8_t *packed2, const float *scales2,
+                     int rows, int cols, uint16_t *dx1_bf16, uint16_t *dx2_bf16, long ldo) {
+  if (!dy_bf16 || !packed1 || !scales1 || !packed2 || !scales2 || !dx1_bf16 || !dx2_bf16)
+    return -1;
+  if (rows < 0 || cols < 0 || ld_dy < cols || ldo < cols) return -2;
+  const int ng = (cols + 127) / 128;
+  for (int r = 0; r < rows; ++r)
+    for (int c = 0; c < cols; ++c) {
+      double dy = (double)bf16_to_f32(dy_bf16[(size_t)r * ld_dy + c]);
+      double x1 = (double)ctx_value(packed1, scales1, ng, r, c);
+      double x2 = (double)ctx_value(packed2, scales2, ng, r, c);
+      double s = 1.0 / (1.0 + exp(-x1));
+      double silu = x1 * s, dsilu = s * (1.0 + x1 * (1.0 - s));
+      dx2_bf16[(size_t)r * ldo + c] = f64_to_bf16_rne(dy * silu);
+      dx1_bf16[(size_t)r * ldo + c] = f64_to_bf16_rne(dy * x2 * dsilu);
+    }
+  return 0;
+}
+
 /* Number of OpenMP threads fqo_gemm will use (1 when built without OpenMP). */
 #ifdef _OPENMP
 #include <omp.h>

@@ -51,6 +51,12 @@ def lib():
         _lib.fqo_ctx_dequantize.restype = C.c_int
         _lib.fqo_ctx_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p,
                                             C.c_long]
+        _lib.fqo_glu_forward.restype = C.c_int
+        _lib.fqo_glu_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_long,
+                                         C.c_void_p, C.c_long]
+        _lib.fqo_glu_backward.restype = C.c_int
+        _lib.fqo_glu_backward.argtypes = [C.c_void_p, C.c_long] + [C.c_void_p] * 4 + \
+                                         [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_long]
         _lib.fqo_threshold_update.restype = C.c_float
         _lib.fqo_threshold_update.argtypes = [C.c_float, C.c_int, C.c_int, C.c_float, C.c_float,
                                               C.c_float]
@@ -193,3 +199,32 @@ def ctx_dequantize(packed: np.ndarray, scales: np.ndarray, rows: int, cols: int)
     if rc != 0:
         raise RuntimeError(f"fqo_ctx_dequantize failed: {rc}")
     return out
+
+
+def glu_forward(x1_bf16: np.ndarray, x2_bf16: np.ndarray):
+    """y = silu(x1) * x2 (Sec. 4.1) as a non-linear layer of Sec. 5.2: returns (y bf16 bits,
+    context of x1, context of x2), each context a (packed, scales) pair of ctx_quantize."""
+    assert x1_bf16.shape == x2_bf16.shape and x1_bf16.dtype == x2_bf16.dtype == np.uint16
+    x1 = np.ascontiguousarray(x1_bf16)
+    x2 = np.ascontiguousarray(x2_bf16)
+    rows, cols = x1.shape
+    y = np.zeros((rows, cols), np.uint16)
+    rc = lib().fqo_glu_forward(x1.ctypes.data, x2.ctypes.data, rows, cols, max(cols, 1),
+                               y.ctypes.data, max(cols, 1))
+    if rc != 0:
+        raise RuntimeError(f"fqo_glu_forward failed: {rc}")
+    return y, ctx_quantize(x1), ctx_quantize(x2)
+
+
+def glu_backward(dy_bf16: np.ndarray, ctx1, ctx2):
+    """(dx1, dx2) bf16 bits from dy and the two INT10 contexts of glu_forward."""
+    dy = np.ascontiguousarray(dy_bf16)
+    rows, cols = dy.shape
+    dx1 = np.zeros((rows, cols), np.uint16)
+    dx2 = np.zeros((rows, cols), np.uint16)
+    rc = lib().fqo_glu_backward(dy.ctypes.data, max(cols, 1), ctx1[0].ctypes.data,
+                                ctx1[1].ctypes.data, ctx2[0].ctypes.data, ctx2[1].ctypes.data,
+                                rows, cols, dx1.ctypes.data, dx2.ctypes.data, max(cols, 1))
+    if rc != 0:
+        raise RuntimeError(f"fqo_glu_backward failed: {rc}")
+    return dx1, dx2
