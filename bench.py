@@ -198,7 +198,29 @@ def context(args):
             "roofline_dequantize": {"bound": "hbm", "achieved": round(nbytes / ms_d / 1e6, 1),
                                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                     "frac": round(nbytes / ms_d / 1e6 / HBM_PEAK_GBS, 4)},
-            "bf16_copy_gbs": round(4.0 * rows * cols / ms_c / 1e6, 1)}
+            "bf16_copy_gbs": round(4.0 * rows * cols / ms_c / 1e6, 1),
+            "glu": glu_times(x)}
+
+
+def glu_times(x):
+    """SiLU-GLU forward and backward with fused INT10 contexts on two tensors of x's shape
+    (stand-ins for the gate and up projections): algorithmic bytes per element pair
+    forward 4 (x1, x2) + 2 (y) + 2*1.28 (contexts) = 8.56, backward 2 (dy) + 2.56 + 4 = 8.56."""
+    import torch
+    import paper_2503_08040_amd as fq
+    rows, cols = x.shape
+    x2 = torch.roll(x, 1, 0).contiguous()
+    y, c1, c2 = fq.fq_glu_forward(x, x2)
+    ms_f = _time_loop(lambda: fq.fq_glu_forward(x, x2), 1.0, 50)
+    ms_b = _time_loop(lambda: fq.fq_glu_backward(y, c1, c2), 1.0, 50)
+    ctx_bytes = 2.0 * (c1[0].numel() + 4.0 * c1[1].numel())
+    fwd_bytes = 6.0 * rows * cols + ctx_bytes
+    bwd_bytes = 6.0 * rows * cols + ctx_bytes
+    return {"ms_forward": round(ms_f, 5), "ms_backward": round(ms_b, 5),
+            "forward_gbs": round(fwd_bytes / ms_f / 1e6, 1),
+            "backward_gbs": round(bwd_bytes / ms_b / 1e6, 1),
+            "forward_frac_of_hbm_peak": round(fwd_bytes / ms_f / 1e6 / HBM_PEAK_GBS, 4),
+            "backward_frac_of_hbm_peak": round(bwd_bytes / ms_b / 1e6 / HBM_PEAK_GBS, 4)}
 
 
 def main():

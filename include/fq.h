@@ -214,6 +214,34 @@ fq_status fq_ctx_dequantize(const uint8_t *packed, const float *scales, int32_t 
                             int32_t cols, void *out_bf16, int64_t ldo, void *hip_stream);
 
 /*
+ * SiLU-gated linear unit y = silu(x1) * x2, silu(x) = x / (1 + e^-x) (Sec. 4.1), as a non-linear
+ * layer of Sec. 5.2: bf16 inputs and output, and in the same pass over x1 and x2 their INT10
+ * contexts (exactly what fq_ctx_quantize would write) for the backward pass.  x1, x2: device,
+ * row-major [rows, ld] bf16; y: [rows, ldy] bf16.  Function values are computed in binary32
+ * with the hardware exponential and reciprocal (about 1 ulp each) and rounded to bf16: a
+ * result is within one bf16 step of the correctly rounded value and equal to it for all but
+ * about one element in a thousand; magnitudes below 2^-100 may come out as zero.
+ * Errors and layouts as fq_ctx_quantize (ld, ldy >= cols).
+ */
+fq_status fq_glu_forward(const void *x1_bf16, const void *x2_bf16, int32_t rows, int32_t cols,
+                         int64_t ld, void *y_bf16, int64_t ldy, uint8_t *ctx1_packed,
+                         float *ctx1_scales, uint8_t *ctx2_packed, float *ctx2_scales,
+                         void *hip_stream);
+
+/*
+ * Backward of fq_glu_forward with the contexts dequantized on the fly (Sec. 5.3): with
+ * x1~ = a*q, x2~ = a*q (one binary32 multiplication each) and s = 1 / (1 + e^-x1~),
+ *   dx2 = dy * x1~ * s,      dx1 = dy * x2~ * s * (1 + x1~ * (1 - s)).
+ * dy: device [rows, ld_dy] bf16; dx1, dx2: device [rows, ldo] bf16.  Accuracy as in the forward
+ * pass, plus an absolute error of up to 2^-20 |dy x2~| in dx1 near the zero of silu'
+ * (x1~ = -1.278), where the factor in parentheses cancels.
+ */
+fq_status fq_glu_backward(const void *dy_bf16, int64_t ld_dy, const uint8_t *ctx1_packed,
+                          const float *ctx1_scales, const uint8_t *ctx2_packed,
+                          const float *ctx2_scales, int32_t rows, int32_t cols, void *dx1_bf16,
+                          void *dx2_bf16, int64_t ldo, void *hip_stream);
+
+/*
  * Fallback block GEMM (Alg. 1).  For every output tile, k-blocks ascending:
  *   C += float(P) * (a^A_ik * a^B_kj),  P the exact INT32 product of the code blocks,
  *   and, if u(i,k) = 1,  C += float(P~) * (a~^A_ik * a^B_kj)  with the residual

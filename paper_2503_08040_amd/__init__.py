@@ -26,7 +26,7 @@ EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr
            "fq_threshold_update", "fq_gemm",
            "fq_gemm_debug_partials", "fq_codes_to_rowmajor", "fq_qtensor_check",
            "fq_status_string", "fq_ctx_packed_bytes", "fq_ctx_scales_bytes", "fq_ctx_quantize",
-           "fq_ctx_dequantize", "fq_gemm_tile_plan"]
+           "fq_ctx_dequantize", "fq_gemm_tile_plan", "fq_glu_forward", "fq_glu_backward"]
 
 
 class fq_qtensor(C.Structure):
@@ -92,6 +92,13 @@ def lib():
         L.fq_ctx_dequantize.restype = C.c_int
         L.fq_ctx_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                         C.c_int64, C.c_void_p]
+        L.fq_glu_forward.restype = C.c_int
+        L.fq_glu_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
+                                     C.c_void_p, C.c_int64] + [C.c_void_p] * 5
+        L.fq_glu_backward.restype = C.c_int
+        L.fq_glu_backward.argtypes = [C.c_void_p, C.c_int64] + [C.c_void_p] * 4 + \
+                                     [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64,
+                                      C.c_void_p]
         L.fq_gemm_tile_plan.restype = C.c_int
         L.fq_gemm_tile_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         _lib = L
@@ -305,3 +312,43 @@ def fq_gemm_tile_plan(rows_out, cols_out, compute_units=0):
     _check(lib().fq_gemm_tile_plan(int(rows_out), int(cols_out), int(compute_units), out),
            "fq_gemm_tile_plan")
     return int(out[0]), int(out[1]), int(out[2])
+
+
+def _pitch(t):
+    rows, cols = t.shape
+    assert t.stride(1) == 1 or cols <= 1
+    return t.stride(0) if rows > 1 else max(cols, 1)
+
+
+def fq_glu_forward(x1, x2, stream=None):
+    """y = silu(x1) * x2 with the INT10 contexts of x1 and x2 written in the same pass.
+    Returns (y bf16, (packed1, scales1), (packed2, scales2))."""
+    import torch
+    assert x1.dtype == x2.dtype == torch.bfloat16 and x1.shape == x2.shape and x1.dim() == 2
+    assert _pitch(x1) == _pitch(x2)
+    rows, cols = x1.shape
+    ng = -(-cols // FQ_CTX_GROUP)
+    y = torch.empty((rows, cols), dtype=torch.bfloat16, device=x1.device)
+    ctx = [(torch.empty((rows, ng, FQ_CTX_GROUP_BYTES), dtype=torch.uint8, device=x1.device),
+            torch.empty((rows, ng), dtype=torch.float32, device=x1.device)) for _ in range(2)]
+    _check(lib().fq_glu_forward(C.c_void_p(x1.data_ptr()), C.c_void_p(x2.data_ptr()), rows, cols,
+                                _pitch(x1), C.c_void_p(y.data_ptr()), _pitch(y),
+                                C.c_void_p(ctx[0][0].data_ptr()), C.c_void_p(ctx[0][1].data_ptr()),
+                                C.c_void_p(ctx[1][0].data_ptr()), C.c_void_p(ctx[1][1].data_ptr()),
+                                _stream_ptr(stream)), "fq_glu_forward")
+    return y, ctx[0], ctx[1]
+
+
+def fq_glu_backward(dy, ctx1, ctx2, stream=None):
+    """(dx1, dx2) bf16 from dy and the two contexts of fq_glu_forward."""
+    import torch
+    assert dy.dtype == torch.bfloat16 and dy.dim() == 2
+    rows, cols = dy.shape
+    dx1 = torch.empty((rows, cols), dtype=torch.bfloat16, device=dy.device)
+    dx2 = torch.empty_like(dx1)
+    _check(lib().fq_glu_backward(C.c_void_p(dy.data_ptr()), _pitch(dy),
+                                 C.c_void_p(ctx1[0].data_ptr()), C.c_void_p(ctx1[1].data_ptr()),
+                                 C.c_void_p(ctx2[0].data_ptr()), C.c_void_p(ctx2[1].data_ptr()),
+                                 rows, cols, C.c_void_p(dx1.data_ptr()), C.c_void_p(dx2.data_ptr()),
+                                 _pitch(dx1), _stream_ptr(stream)), "fq_glu_backward")
+    return dx1, dx2

@@ -242,6 +242,57 @@ fq_status fq_ctx_dequantize(const uint8_t* packed, const float* scales, int32_t 
   return ctx_impl(nullptr, 0, out_bf16, ldo, packed, scales, rows, cols, true, hip_stream);
 }
 
+namespace {
+inline bool bf16_vec_ok(const void* ptr, int64_t pitch) {
+  return ((uintptr_t)ptr & 15) == 0 && (pitch % 8) == 0;
+}
+}  // namespace
+
+fq_status fq_glu_forward(const void* x1_bf16, const void* x2_bf16, int32_t rows, int32_t cols,
+                         int64_t ld, void* y_bf16, int64_t ldy, uint8_t* ctx1_packed,
+                         float* ctx1_scales, uint8_t* ctx2_packed, float* ctx2_scales,
+                         void* hip_stream) {
+  const int64_t n = ctx_groups(rows, cols);
+  if (n < 0 || ld < cols || ldy < cols) return FQ_ERR_SHAPE;
+  if (n == 0) return FQ_OK;
+  if (!x1_bf16 || !x2_bf16 || !y_bf16 || !ctx1_packed || !ctx1_scales || !ctx2_packed ||
+      !ctx2_scales)
+    return FQ_ERR_NULL;
+  if (((uintptr_t)ctx1_packed | (uintptr_t)ctx2_packed) & 3) return FQ_ERR_SHAPE;
+  fq::GluParams p{};
+  p.x1 = static_cast<const uint16_t*>(x1_bf16); p.x2 = static_cast<const uint16_t*>(x2_bf16);
+  p.ld = ld; p.y = static_cast<uint16_t*>(y_bf16); p.ldy = ldy;
+  p.packed1 = ctx1_packed; p.scales1 = ctx1_scales; p.packed2 = ctx2_packed; p.scales2 = ctx2_scales;
+  p.cols = cols; p.ng = (int)ceil_div(cols, FQ_CTX_GROUP); p.n_groups = n;
+  p.vec_ok = bf16_vec_ok(x1_bf16, ld) && bf16_vec_ok(x2_bf16, ld) && bf16_vec_ok(y_bf16, ldy);
+  if (fq::launch_glu(p, false, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return FQ_ERR_HIP;
+  return FQ_OK;
+}
+
+fq_status fq_glu_backward(const void* dy_bf16, int64_t ld_dy, const uint8_t* ctx1_packed,
+                          const float* ctx1_scales, const uint8_t* ctx2_packed,
+                          const float* ctx2_scales, int32_t rows, int32_t cols, void* dx1_bf16,
+                          void* dx2_bf16, int64_t ldo, void* hip_stream) {
+  const int64_t n = ctx_groups(rows, cols);
+  if (n < 0 || ld_dy < cols || ldo < cols) return FQ_ERR_SHAPE;
+  if (n == 0) return FQ_OK;
+  if (!dy_bf16 || !dx1_bf16 || !dx2_bf16 || !ctx1_packed || !ctx1_scales || !ctx2_packed ||
+      !ctx2_scales)
+    return FQ_ERR_NULL;
+  if (((uintptr_t)ctx1_packed | (uintptr_t)ctx2_packed) & 3) return FQ_ERR_SHAPE;
+  fq::GluParams p{};
+  p.dy = static_cast<const uint16_t*>(dy_bf16); p.ld_dy = ld_dy;
+  p.dx1 = static_cast<uint16_t*>(dx1_bf16); p.dx2 = static_cast<uint16_t*>(dx2_bf16); p.ldo = ldo;
+  p.packed1 = const_cast<uint8_t*>(ctx1_packed); p.scales1 = const_cast<float*>(ctx1_scales);
+  p.packed2 = const_cast<uint8_t*>(ctx2_packed); p.scales2 = const_cast<float*>(ctx2_scales);
+  p.cols = cols; p.ng = (int)ceil_div(cols, FQ_CTX_GROUP); p.n_groups = n;
+  p.vec_ok = bf16_vec_ok(dy_bf16, ld_dy) && bf16_vec_ok(dx1_bf16, ldo) && bf16_vec_ok(dx2_bf16, ldo);
+  if (fq::launch_glu(p, true, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return FQ_ERR_HIP;
+  return FQ_OK;
+}
+
 fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,
                   int64_t ldc, void* hip_stream) {
   fq::GemmParams g;

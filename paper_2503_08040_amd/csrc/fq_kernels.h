@@ -71,12 +71,35 @@ struct CtxParams {
   int vec_ok;          // the bf16 side allows 16-byte accesses
 };
 
+// SiLU-gated linear unit with fused INT10 contexts (forward: x1, x2 -> y, contexts; backward:
+// dy, contexts -> dx1, dx2).  All bf16 matrices are row-major [rows, pitch].
+struct GluParams {
+  const uint16_t* x1;
+  const uint16_t* x2;
+  int64_t ld;          // pitch of x1 and x2
+  uint16_t* y;
+  int64_t ldy;
+  const uint16_t* dy;
+  int64_t ld_dy;
+  uint16_t* dx1;
+  uint16_t* dx2;
+  int64_t ldo;         // pitch of dx1 and dx2
+  uint8_t* packed1;
+  float* scales1;
+  uint8_t* packed2;
+  float* scales2;
+  int cols, ng;
+  int64_t n_groups;
+  int vec_ok;          // every bf16 matrix of the call allows 16-byte accesses
+};
+
 hipError_t launch_quantize(const QuantParams& p, hipStream_t st);
 hipError_t launch_untile(const int8_t* tiled, int rows, int cols, int8_t* dense, hipStream_t st);
 hipError_t launch_gemm(const GemmParams& p, bool debug, hipStream_t st);
 // out = {workgroups with 2x2-block tiles, tile columns they cover, 1x3-block tile columns};
 // cus <= 0: the current device's compute units (or FQ_GEMM_CUS).
 void gemm_tile_plan(int nib, int njb, int cus, int out[3]);
+hipError_t launch_glu(const GluParams& p, bool backward, hipStream_t st);
 hipError_t launch_ctx(const CtxParams& p, bool dequantize, hipStream_t st);
 
 }  // namespace fq
