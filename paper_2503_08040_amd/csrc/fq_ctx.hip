@@ -108,12 +108,13 @@ __device__ inline void quantize_store(const float (&x)[kValsPerLane], const Lane
   amax = fmaxf(amax, __shfl_xor(amax, 2, 64));
   amax = fmaxf(amax, __shfl_xor(amax, 4, 64));
   const float a = __fdiv_rn(amax, 511.0f);
+  const float a_rcp = fast_recip(a);
 
   uint32_t w[5] = {0, 0, 0, 0, 0};
   if (a != 0.0f) {
 #pragma unroll
     for (int i = 0; i < kValsPerLane; ++i) {
-      float t = rintf(__fdiv_rn(x[i], a));
+      float t = rint_quotient(x[i], a, a_rcp);
       t = fminf(fmaxf(t, -511.0f), 511.0f);
       const uint32_t bits = (uint32_t)(int)t & 0x3FFu;
       const int pos = 10 * i, word = pos >> 5, sh = pos & 31;

@@ -52,9 +52,9 @@ __device__ inline void block_sum2(double& a, double& b, double* red) {
   b = (red[4] + red[5]) + (red[6] + red[7]);
 }
 
-// round-to-nearest-even of x/a with a correctly rounded division, clamped.
-__device__ inline int quantize_one(float x, float a) {
-  float t = rintf(__fdiv_rn(x, a));
+// round-to-nearest-even of the correctly rounded quotient x/a (r = fast_recip(a)), clamped.
+__device__ inline int quantize_one(float x, float a, float r) {
+  float t = rint_quotient(x, a, r);
   t = fminf(fmaxf(t, -127.0f), 127.0f);
   return (int)t;
 }
@@ -87,26 +87,43 @@ __device__ inline int quantize_one_sr(float x, float a, uint32_t w) {
   return (int)v;
 }
 
-__device__ inline v4i pack16(const int* q) {
-  v4i o;
+// Register state of a thread: its 4 x 16 input values stay in the packed bf16 form they were
+// loaded in (raw[pz][half][dword], two values per dword, low half first) and its codes in
+// packed bytes (4 per dword).  Keeping both packed holds the kernel under 128 VGPRs, i.e. four
+// workgroups per compute unit: on the tensors this kernel sees (a thousand blocks or so) that
+// is the difference between one round of workgroups and a second, nearly empty one.
+__device__ inline float x_at(const v4i (&raw)[4][2], int pz, int e) {
+  const uint32_t w = (uint32_t)raw[pz][e >> 3][(e & 7) >> 1];
+  return __uint_as_float((e & 1) ? (w & 0xFFFF0000u) : (w << 16));
+}
+
+__device__ inline int code_at(const v4i (&q)[4], int pz, int e) {
+  return (int)(int8_t)((uint32_t)q[pz][e >> 2] >> (8 * (e & 3)));
+}
+
+// Makes the packed inputs opaque to the optimizer at this point, so that values unpacked
+// before it are not kept alive across it (they are cheap to unpack again); emits no code.
+__device__ __forceinline__ void forget_unpacked(v4i (&raw)[4][2]) {
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
-    o[w] = (q[4 * w] & 0xFF) | ((q[4 * w + 1] & 0xFF) << 8) | ((q[4 * w + 2] & 0xFF) << 16) |
-           ((q[4 * w + 3] & 0xFF) << 24);
-  }
-  return o;
+  for (int pz = 0; pz < 4; ++pz) asm volatile("" : "+v"(raw[pz][0]), "+v"(raw[pz][1]));
+}
+
+__device__ inline void put_code(v4i& q, int e, int code) {
+  const int sh = 8 * (e & 3);
+  if (sh == 0) q[e >> 2] = code & 0xFF;          // first byte of the dword: no read-modify
+  else q[e >> 2] |= (code & 0xFF) << sh;
 }
 
 // Writes this thread's 4x16 codes into an LDS image of the transposed block in
 // tile order, then the workgroup copies the image out linearly.
-__device__ inline void store_transposed(const int (&q)[4][16], int rp, int cc, int8_t* img,
+__device__ inline void store_transposed(const v4i (&q)[4], int rp, int cc, int8_t* img,
                                         int8_t* dst) {
   __syncthreads();
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     int r = p * 32 + rp;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) img[tile_offset(cc * 16 + e, r)] = (int8_t)q[p][e];
+    for (int e = 0; e < 16; ++e) img[tile_offset(cc * 16 + e, r)] = (int8_t)code_at(q, p, e);
   }
   __syncthreads();
   const v4i* src = reinterpret_cast<const v4i*>(img);
@@ -120,7 +137,7 @@ __device__ inline void store_transposed(const int (&q)[4][16], int rp, int cc, i
 // kErr: the fallback decision uses a block quantization-error metric (criteria 3, 4), which
 // needs the residual of every block, not only of the flagged ones.
 template <bool kWantT, bool kStochastic, bool kErr>
-__global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
+__global__ __launch_bounds__(kThreads, 4) void quantize_kernel(QuantParams p) {
   __shared__ float red[4];
   __shared__ double redd[kErr ? 8 : 1];
   __shared__ int slot_sh;
@@ -133,31 +150,28 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
   const int row0 = bi * kBlock, col0 = bk * kBlock + cc * 16;
 
   // ---- load 4 x 16 bf16, zero outside the matrix
-  float x[4][16];
+  v4i raw[4][2];
   const bool inner = (row0 + kBlock <= p.rows) && (bk * kBlock + kBlock <= p.cols) && p.vec_ok;
   if (inner) {
 #pragma unroll
     for (int pz = 0; pz < 4; ++pz) {
       const uint16_t* src = p.x + (int64_t)(row0 + pz * 32 + rp) * p.ld + col0;
-      v4i lo = *reinterpret_cast<const v4i*>(src);
-      v4i hi = *reinterpret_cast<const v4i*>(src + 8);
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        x[pz][2 * w] = bf16_bits_to_float((uint32_t)lo[w] & 0xFFFFu);
-        x[pz][2 * w + 1] = __uint_as_float((uint32_t)lo[w] & 0xFFFF0000u);
-        x[pz][8 + 2 * w] = bf16_bits_to_float((uint32_t)hi[w] & 0xFFFFu);
-        x[pz][8 + 2 * w + 1] = __uint_as_float((uint32_t)hi[w] & 0xFFFF0000u);
-      }
+      raw[pz][0] = *reinterpret_cast<const v4i*>(src);
+      raw[pz][1] = *reinterpret_cast<const v4i*>(src + 8);
     }
   } else {
 #pragma unroll
     for (int pz = 0; pz < 4; ++pz) {
       const int r = row0 + pz * 32 + rp;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int c = col0 + e;
-        x[pz][e] = (r < p.rows && c < p.cols)
-                       ? bf16_bits_to_float(p.x[(int64_t)r * p.ld + c]) : 0.0f;
+      for (int d = 0; d < 8; ++d) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const int c = col0 + 2 * d + hh;
+          if (r < p.rows && c < p.cols) w |= (uint32_t)p.x[(int64_t)r * p.ld + c] << (16 * hh);
+        }
+        raw[pz][d >> 2][d & 3] = (int)w;
       }
     }
   }
@@ -167,16 +181,32 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
 #pragma unroll
   for (int pz = 0; pz < 4; ++pz)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) m = fmaxf(m, fabsf(x[pz][e]));
+    for (int e = 0; e < 16; ++e) m = fmaxf(m, fabsf(x_at(raw, pz, e)));
   const float amax = block_max(m, red);
   const float a = __fdiv_rn(amax, 127.0f);
+  const float a_rcp = fast_recip(a);
+  forget_unpacked(raw);
 
-  int q[4][16];
+  // The abs-max decision is known now: take the residual slot right away, so that the round
+  // trip of the atomic is hidden behind the quantization of the block.          (Sec. 4.4)
+  bool u = false;
+  int slot_early = -1;
+  if (!kErr) {
+    u = p.crit == 2 || (p.crit == 1 && amax > p.theta);
+    if (u && t == 0) slot_early = atomicAdd(p.fb_count, 1);
+  }
+
+  v4i q[4];
   if (!kStochastic) {
 #pragma unroll
-    for (int pz = 0; pz < 4; ++pz)
+    for (int pz = 0; pz < 4; ++pz) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) q[pz][e] = (a == 0.0f) ? 0 : quantize_one(x[pz][e], a);
+      for (int e = 0; e < 16; ++e) {
+        put_code(q[pz], e, (a == 0.0f) ? 0 : quantize_one(x_at(raw, pz, e), a, a_rcp));
+        // eight divisions in flight at a time: bounds the live temporaries
+        if ((e & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+      }
+    }
   } else {
     // element (r, c) uses word (r*cols + c) & 3 of the Philox block with counter (r*cols + c) >> 2
     const uint32_t k0 = (uint32_t)p.seed, k1 = (uint32_t)(p.seed >> 32);
@@ -191,7 +221,8 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
           philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), k0, k1, w);
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            q[pz][4 * b + i] = (a == 0.0f) ? 0 : quantize_one_sr(x[pz][4 * b + i], a, w[i]);
+            put_code(q[pz], 4 * b + i,
+                     (a == 0.0f) ? 0 : quantize_one_sr(x_at(raw, pz, 4 * b + i), a, w[i]));
         }
       } else {               // row pitch not a multiple of 4: one block per element
 #pragma unroll
@@ -199,21 +230,26 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
           uint32_t w[4];
           const uint64_t el = e0 + e, ctr = el >> 2;
           philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), k0, k1, w);
-          q[pz][e] = (a == 0.0f) ? 0 : quantize_one_sr(x[pz][e], a, w[el & 3]);
+          put_code(q[pz], e, (a == 0.0f) ? 0 : quantize_one_sr(x_at(raw, pz, e), a, w[el & 3]));
         }
       }
     }
   }
 
+  forget_unpacked(raw);
   int8_t* cdst = p.codes + (int64_t)blk * kBlockBytes;
 #pragma unroll
   for (int pz = 0; pz < 4; ++pz)
-    *reinterpret_cast<v4i*>(cdst + tile_offset(pz * 32 + rp, cc * 16)) = pack16(q[pz]);
+    *reinterpret_cast<v4i*>(cdst + tile_offset(pz * 32 + rp, cc * 16)) = q[pz];
   if (kWantT)
     store_transposed(q, rp, cc, img, p.codes_t + ((int64_t)bk * p.nbr + bi) * kBlockBytes);
 
-  // ---- fallback decision                                         (Sec. 4.4)
-  bool u;
+  // the residual G - a*codes of element (pz, e): one fused multiply-add, single rounding
+  auto residual = [&](int pz, int e) {
+    return __builtin_fmaf(-(float)code_at(q, pz, e), a, x_at(raw, pz, e));
+  };
+
+  // ---- fallback decision by a quantization-error metric          (Sec. 4.4)
   if (kErr) {
     // L1 = sum |G - Q(G)| over the block, L1-Rel = L1 / sum |G|; the sums are binary64
     // accumulations of the binary32 terms (order unspecified), compared with theta in binary64
@@ -222,23 +258,18 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
     for (int pz = 0; pz < 4; ++pz)
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        l1x += (double)fabsf(x[pz][e]);
-        x[pz][e] = __builtin_fmaf(-(float)q[pz][e], a, x[pz][e]);
-        l1 += (double)fabsf(x[pz][e]);
+        l1x += (double)fabsf(x_at(raw, pz, e));
+        l1 += (double)fabsf(residual(pz, e));
       }
     block_sum2(l1, l1x, redd);
     if (p.crit == 3) u = l1 > (double)p.theta;
     else u = l1x > 0.0 && l1 / l1x > (double)p.theta;
-  } else if (p.crit == 0) u = false;
-  else if (p.crit == 2) u = true;
-  else u = amax > p.theta;
+    if (u && t == 0) slot_early = atomicAdd(p.fb_count, 1);
+  }
 
   int slot = -1;
   if (u) {
-    if (t == 0) {
-      int s = atomicAdd(p.fb_count, 1);
-      slot_sh = (s < p.capacity) ? s : -2;
-    }
+    if (t == 0) slot_sh = (slot_early < p.capacity) ? slot_early : -2;
     __syncthreads();
     slot = slot_sh;
   }
@@ -252,26 +283,31 @@ __global__ __launch_bounds__(kThreads) void quantize_kernel(QuantParams p) {
   if (slot < 0) return;  // uniform over the workgroup
 
   // ---- step 2: quantize the residual G - a*codes                 (Sec. 4.3)
+  // (the residual is recomputed where it is needed instead of being kept in 64 registers)
   float rm = 0.0f;
 #pragma unroll
   for (int pz = 0; pz < 4; ++pz)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      if (!kErr) x[pz][e] = __builtin_fmaf(-(float)q[pz][e], a, x[pz][e]);
-      rm = fmaxf(rm, fabsf(x[pz][e]));
-    }
+    for (int e = 0; e < 16; ++e) rm = fmaxf(rm, fabsf(residual(pz, e)));
   const float rmax = block_max(rm, red);
   const float ra = __fdiv_rn(rmax, 127.0f);
+  const float ra_rcp = fast_recip(ra);
+  forget_unpacked(raw);
+  v4i rq[4];
 #pragma unroll
-  for (int pz = 0; pz < 4; ++pz)
+  for (int pz = 0; pz < 4; ++pz) {
 #pragma unroll
-    for (int e = 0; e < 16; ++e) q[pz][e] = (ra == 0.0f) ? 0 : quantize_one(x[pz][e], ra);
+    for (int e = 0; e < 16; ++e) {
+      put_code(rq[pz], e, (ra == 0.0f) ? 0 : quantize_one(residual(pz, e), ra, ra_rcp));
+      if ((e & 7) == 7) __builtin_amdgcn_sched_barrier(0);
+    }
+  }
 
   int8_t* rdst = p.res_codes + (int64_t)slot * kBlockBytes;
 #pragma unroll
   for (int pz = 0; pz < 4; ++pz)
-    *reinterpret_cast<v4i*>(rdst + tile_offset(pz * 32 + rp, cc * 16)) = pack16(q[pz]);
-  if (kWantT) store_transposed(q, rp, cc, img, p.res_codes_t + (int64_t)slot * kBlockBytes);
+    *reinterpret_cast<v4i*>(rdst + tile_offset(pz * 32 + rp, cc * 16)) = rq[pz];
+  if (kWantT) store_transposed(rq, rp, cc, img, p.res_codes_t + (int64_t)slot * kBlockBytes);
   if (t == 0) p.res_scales[slot] = ra;
 }
 
