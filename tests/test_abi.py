@@ -119,3 +119,35 @@ def test_untile_rejects_bad_arguments():
     assert L.fq_codes_to_rowmajor(None, 4, 4, C.c_void_p(0x10), None) == fq.FQ_ERR_NULL
     assert L.fq_codes_to_rowmajor(C.c_void_p(0x10), -4, 4, C.c_void_p(0x10), None) == fq.FQ_ERR_SHAPE
     assert L.fq_codes_to_rowmajor(None, 0, 4, None, None) == fq.FQ_OK
+
+
+def test_tile_plan_covers_the_output_and_never_costs_more():
+    """fq_gemm_tile_plan (host-only): 256x256 tiles over the first block columns, 128x384 tiles
+    over the rest; every block column is covered exactly once, and the plan is only split when
+    that shortens the last round (costs in units of one 256x256 tile per compute unit)."""
+    import itertools
+    import random
+    rng = random.Random(0)
+    cases = [(4096, 11008, 256), (8192, 8192, 256), (4096, 4096, 256), (11008, 4096, 256), (1, 1, 256)]
+    cases += [(rng.randint(1, 6000), rng.randint(1, 14000), rng.choice([1, 3, 8, 64, 256, 304]))
+              for _ in range(300)]
+    split = 0
+    for rows, cols, cus in cases:
+        n_main, main_tj, tail_tj = fq.fq_gemm_tile_plan(rows, cols, cus)
+        nib, njb = -(-rows // 128), -(-cols // 128)
+        tiles_i, tiles_j = -(-nib // 2), -(-njb // 2)
+        assert n_main == tiles_i * main_tj and 0 <= main_tj <= tiles_j and tail_tj >= 0
+        if tail_tj == 0:
+            assert main_tj == tiles_j
+            continue
+        split += 1
+        tail_cols = njb - 2 * main_tj
+        assert tail_cols > 0 and 3 * (tail_tj - 1) < tail_cols <= 3 * tail_tj
+        rounds = lambda n: -(-n // cus)
+        assert rounds(n_main) + 0.75 * rounds(nib * tail_tj) < rounds(tiles_i * tiles_j)
+    assert split > 10
+    assert fq.fq_gemm_tile_plan(4096, 11008, 256) == (512, 32, 8)
+    assert fq.fq_gemm_tile_plan(8192, 8192, 256) == (1024, 32, 0)
+    p = (C.c_int32 * 3)()
+    assert fq.lib().fq_gemm_tile_plan(-1, 5, 4, p) == fq.FQ_ERR_SHAPE
+    assert fq.lib().fq_gemm_tile_plan(5, 5, 4, None) == fq.FQ_ERR_NULL
