@@ -35,9 +35,11 @@
  *   (bi, bk) occupies the 16384 bytes starting at (bi*nbc + bk)*16384, and
  *   element (r, c) of the block (0 <= r, c < 128) is the byte at
  *       ((r/32)*4 + c/32)*1024 + ((r%32) + 32*((c%32)/16))*16 + c%16 .
- *   This is the operand order of the gfx950 INT8 matrix instruction
- *   (32x32x32): every 1 KiB run is one wavefront-wide operand fragment, 16
- *   contraction-contiguous bytes per lane, so the GEMM streams blocks with
+ *   Every 16-byte run holds 16 contraction-contiguous codes of one row, and rows follow each
+ *   other at 16-byte steps inside a 1 KiB run of 32 rows x 32 contraction positions: the
+ *   operands of the gfx950 INT8 matrix instructions (16 contraction-contiguous bytes per lane,
+ *   consecutive lanes = consecutive rows) are whole 256- or 512-byte runs of this order, so the
+ *   GEMM moves blocks with
  *   perfectly coalesced 16-byte accesses and no shuffling.  Padding elements
  *   of edge blocks are stored as 0.  `codes_t` holds the transposed matrix
  *   (cols x rows) in the same order; it is what the backward products read

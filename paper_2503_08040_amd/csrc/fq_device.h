@@ -7,7 +7,7 @@ namespace fq {
 
 constexpr int kBlock = 128;          // quantization block edge (Sec. 4.5 of the paper)
 constexpr int kBlockBytes = 16384;   // one block of INT8 codes
-constexpr int kFragBytes = 1024;     // one wavefront-wide 32x32 operand fragment
+constexpr int kFragBytes = 1024;     // one 32-row x 32-deep run of a block in tile order
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));

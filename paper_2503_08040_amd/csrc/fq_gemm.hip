@@ -25,9 +25,11 @@
 //     loads every wavefront equally;
 //   - operands reach LDS by direct global->LDS 16-byte loads (blocks are stored
 //     in operand order, see fq.h), one barrier per item;
-//   - per 32 x 32 sub-tile: 4 v_mfma_i32_32x32x32_i8 (K = 128) into an INT32
-//     tile, then one convert + one FMA per element folds it into the FP32
-//     accumulators with the scalar scale of that block pair.
+//   - per 32 x 32 sub-tile: 8 v_mfma_i32_16x16x64_i8 (four 16 x 16 quadrants x
+//     two halves of K = 128) into an INT32 tile, then one convert + one FMA per
+//     element folds it into the FP32 accumulators with the scalar scale of that
+//     block pair.  (The 16x16x64 form sustains a third more than 32x32x32 on this
+//     part and leaves the dequantizing pipeline about 10 % faster.)
 // The accumulation order per output element is exactly Alg. 1's (k ascending,
 // main term then residual term) in both geometries, so results match a
 // sequential evaluation bit for bit and do not depend on the tile plan.
@@ -81,8 +83,14 @@ __device__ inline int pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(int, __builtin_convertvector(v, bf16x2));
 }
 
-__device__ inline v4i lds_frag(const int8_t* blk, int rg, int ks, int lane) {
-  return *reinterpret_cast<const v4i*>(blk + ((rg * 4 + ks) * 64 + lane) * 16);
+// One operand of v_mfma_i32_16x16x64_i8 out of a block stored in tile order: rows (or
+// columns) [32 rg + 16 rh, +16), contraction [64 ks, +64).  Lane l supplies row l % 16 and the
+// 16 contraction-contiguous bytes of group l / 16, i.e. the bytes at tile_offset(row, 64 ks +
+// 16 (l / 16)): whole 256-byte runs per 16 lanes, conflict-free.  The order of the contraction
+// inside the instruction does not matter as long as both operands use the same one.
+__device__ inline v4i lds_frag(const int8_t* blk, int rg, int rh, int ks, int lane) {
+  return *reinterpret_cast<const v4i*>(blk + ((rg * 4 + ks * 2) * 64 + rh * 16) * 16 +
+                                       (lane + 16 * (lane >> 4)) * 16);
 }
 
 
@@ -90,10 +98,8 @@ __device__ inline v4i lds_frag(const int8_t* blk, int rg, int ks, int lane) {
 // compiler may not reorder volatile asm, so the instructions producing the operands stay
 // before the statement and their consumers after it: this pins the source order of otherwise
 // freely movable pure instructions (MFMA, convert, FMA) without emitting any code.
-__device__ __forceinline__ void pin(v16i& x) { asm volatile("" : "+v"(x)); }
-__device__ __forceinline__ void pin(float& a, float& b, float& c, float& d) {
-  asm volatile("" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
-}
+__device__ __forceinline__ void pin(v4i& x) { asm volatile("" : "+v"(x)); }
+__device__ __forceinline__ void pin(float& a, float& b) { asm volatile("" : "+v"(a), "+v"(b)); }
 
 // Geometry of a workgroup tile: kBI x kBJ quantization blocks, computed by 8 wavefronts laid
 // out 2 (row halves h) x 4 (column groups c).  Wavefront (h, c) owns rows [64h, 64h+64) of every
@@ -114,7 +120,7 @@ struct Geo {
   static constexpr int kSC = (kBJ == 2) ? 1 : kSJ;  // distinct scale columns per i-block
   static constexpr int kSP = (kBJ == 2) ? 1 : 2;    // distinct scales of an item's last two units
   static constexpr int kStageCols = 32 * kSJ;
-  static constexpr int kStagePitch = kStageCols + 8;   // floats per staged row: conflict-free
+  static constexpr int kStagePitch = kStageCols + 4;   // floats per staged row: 4 rows apart = 16 banks apart
   static constexpr int kStageBytesPerWave = 32 * kStagePitch * 4;
   static_assert(2 * (kASet + kBSet) <= kLdsBytes, "operand rings must fit");
   static_assert(8 * kStageBytesPerWave <= kLdsBytes, "epilogue staging must fit");
@@ -124,11 +130,13 @@ struct Geo {
 // Per-wavefront register state of the k-loop.
 template <class G>
 struct WaveState {
-  float acc[G::kSI][G::kSJ][16];   // FP32 accumulators: sub-tile (si, sj), 16 elements per lane
-  v4i aq[2][4];                    // A fragments (ks = 0..3) of two consecutive si: si uses aq[si & 1]
-  v4i bq[G::kSJ][4];               // B fragments of this wave's column groups
-  v16i P[2];                       // INT32 tiles: sub-tile u accumulates into P[u & 1]
-  float T[4];                      // elements converted in the previous slot, waiting for their FMA
+  // FP32 accumulators: sub-tile (si, sj), 16 elements per lane; element 4 q + r belongs to
+  // quadrant q = 2 rh + ch of the sub-tile: row 16 rh + 4 (lane / 16) + r, column 16 ch + lane % 16
+  float acc[G::kSI][G::kSJ][16];
+  v4i aq[2][2][2];                 // A operands [rh][ks] of two consecutive si: si uses aq[si & 1]
+  v4i bq[G::kSJ][2][2];            // B operands [ch][ks] of this wave's column groups
+  v4i P[2][4];                     // INT32 quadrants: sub-tile u accumulates into P[u & 1]
+  float T[2];                      // elements converted in the previous slot, waiting for their FMA
 };
 
 // Scales of one item as the units see them: s[bi][sc] = a^A (or a~^A) of i-block bi times a^B
@@ -139,16 +147,18 @@ struct ItemScales {
 };
 
 // The k-loop is one continuous software pipeline over sub-tiles ("units": u = kSJ*si + sj).
-// Unit u is 4 slots; slot g issues MFMA g (K = 32 of the 128) of unit u and, in the 32
-// cycles the matrix core needs for it, 8 vector-ALU instructions that fold the finished INT32
-// tile of unit u-1 into the FP32 accumulators: the 4 FMAs of the elements converted one slot
-// earlier, then the 4 converts of elements 4g..4g+3.  An FMA never waits for its convert, and a
-// convert reads an MFMA result that is at least 11 issue slots old, as the hardware requires.
-// Fragment registers are refilled from LDS well before their next use: the A fragments of si+1
-// are fetched into a second register buffer while si is being multiplied (LDS latency under
-// load is several hundred cycles), and the last two units fetch the B fragments and the first
-// A fragments of the NEXT item, so that no item starts with a burst of LDS reads.  Scheduling
-// fences pin this order.
+// A unit is 8 slots.  Slot n issues one v_mfma_i32_16x16x64_i8 of unit u: contraction half
+// ks = n / 4 of quadrant q = n % 4 (q = 2 rh + ch: row half rh, column half ch of the 32 x 32
+// sub-tile), so the two MFMAs that accumulate into the same quadrant are four slots apart.  In
+// the 16 cycles the matrix core needs for it the slot also issues 4 vector-ALU instructions that
+// fold the finished INT32 tile of unit u-1 into the FP32 accumulators: the 2 FMAs of the
+// elements converted one slot earlier, then the 2 converts of elements 2n, 2n+1.  An FMA never
+// waits for its convert, and a convert reads a quadrant whose last MFMA is at least four slots
+// old.  Operand registers are refilled from LDS well before their next use: the A operands of
+// si+1 are fetched into a second register buffer while si is being multiplied (LDS latency
+// under load is several hundred cycles), and the last two units fetch the B operands and the
+// first A operands of the NEXT item (a B operand right after its last use), so that no item
+// starts with a burst of LDS reads.  Scheduling fences pin this order.
 //   a_cur: A set of the current item in LDS; a_nxt / b_nxt: A set / B set of the next item.
 //   sc: scales of the current item; sp: scales of the previous item's last two units.
 //   h, c: this wavefront's row half and column group.
@@ -158,56 +168,58 @@ __device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, 
                                          const ItemScales<G>& sc, const float (&sp)[G::kSP]) {
   constexpr int kSJ = G::kSJ, kUnits = G::kUnits;
   constexpr int si = u / kSJ, sj = u % kSJ;
-  // B fragments of column group cg = kSJ*c + sj of the tile: block cg / 4, row group cg % 4
-  auto b_frag = [&](int j, int g) {
+  // B operand (ch, ks) of column group cg = kSJ*c + j of the tile: block cg / 4, group cg % 4
+  auto b_frag = [&](int j, int ch, int ks) {
     const int cg = kSJ * c + j;
-    return lds_frag(b_nxt + (cg >> 2) * kBlockBytes, cg & 3, g, lane);
+    return lds_frag(b_nxt + (cg >> 2) * kBlockBytes, cg & 3, ch, ks, lane);
   };
 #pragma unroll
-  for (int g = 0; g < 4; ++g) {
+  for (int n = 0; n < 8; ++n) {
+    constexpr int kDummy = 0;
+    (void)kDummy;
+    const int ks = n >> 2, rh = (n >> 1) & 1, ch = n & 1, q = 2 * rh + ch;
     {
-      const v16i z = {0};
-      st.P[u & 1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(st.aq[si & 1][g], st.bq[sj][g],
-                                                          g ? st.P[u & 1] : z, 0, 0, 0);
-      // A fragments of the next si go into the other aq buffer a whole unit before their
-      // first use
-      if (si + 1 < G::kSI && sj == 0)
-        st.aq[(si + 1) & 1][g] =
-            lds_frag(a_cur + ((si + 1) >> 1) * kBlockBytes, 2 * h + ((si + 1) & 1), g, lane);
-      // the last two units (same si, odd: they use aq[1]) fetch the next item's first fragments;
-      // a bq buffer is refilled right after its last use
+      const v4i z = {0, 0, 0, 0};
+      st.P[u & 1][q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
+          st.aq[si & 1][rh][ks], st.bq[sj][ch][ks], ks ? st.P[u & 1][q] : z, 0, 0, 0);
+      // B operand (ch, ks) was used for the last time in the slot with rh = 1
+      const bool b_done = rh == 1;
+      // the other four slots (rh = 0) carry a load each into a free buffer: operand i = 0..3
+      const int i = 2 * ks + ch, irh = i >> 1, iks = i & 1;
+      // A operands of the next si go into the other aq buffer a whole unit before their use
+      if (si + 1 < G::kSI && sj == 0 && !b_done)
+        st.aq[(si + 1) & 1][irh][iks] = lds_frag(a_cur + ((si + 1) >> 1) * kBlockBytes,
+                                                 2 * h + ((si + 1) & 1), irh, iks, lane);
+      // the last two units (same si, odd: they use aq[1]) fetch the next item's first operands
       if (u == kUnits - 2) {
-        st.aq[0][g] = lds_frag(a_nxt, 2 * h, g, lane);
-        st.bq[sj][g] = b_frag(sj, g);
+        if (b_done) st.bq[sj][ch][ks] = b_frag(sj, ch, ks);
+        else st.aq[0][irh][iks] = lds_frag(a_nxt, 2 * h, irh, iks, lane);
       }
       if (u == kUnits - 1) {
-        st.bq[sj][g] = b_frag(sj, g);
-#pragma unroll
-        for (int j = 0; j + 2 < kSJ; ++j) st.bq[j][g] = b_frag(j, g);
+        if (b_done) st.bq[sj][ch][ks] = b_frag(sj, ch, ks);
+        else if (kSJ == 3) st.bq[0][irh][iks] = b_frag(0, irh, iks);
       }
-      pin(st.P[u & 1]);
+      pin(st.P[u & 1][q]);
     }
     __builtin_amdgcn_sched_barrier(0);   // MFMA first: its destination must not alias live tiles
     {
-      // FMAs of the 4 elements converted in the previous slot (unit u-1, or u-2 for g = 0);
+      // FMAs of the 2 elements converted in the previous slot (unit u-1, or u-2 for n = 0);
       // negative units are the last two units of the previous item
       constexpr int kLastSi = G::kSI - 1;
-      const int fu = g ? u - 1 : u - 2, fc = g ? g - 1 : 3;
+      const int fu = n ? u - 1 : u - 2, fe = n ? 2 * (n - 1) : 14;
       const bool prev = fu < 0;
       const int pu = fu + kUnits;                       // unit index in the previous item
       const int fsi = prev ? kLastSi : fu / kSJ, fsj = prev ? pu % kSJ : fu % kSJ;
       const float s = prev ? sp[G::kSP == 1 ? 0 : pu - (kUnits - 2)]
                            : sc.s[fsi >> 1][G::kSC == 1 ? 0 : fsj];
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        st.acc[fsi][fsj][4 * fc + i] = __builtin_fmaf(st.T[i], s, st.acc[fsi][fsj][4 * fc + i]);
-      pin(st.acc[fsi][fsj][4 * fc], st.acc[fsi][fsj][4 * fc + 1], st.acc[fsi][fsj][4 * fc + 2],
-          st.acc[fsi][fsj][4 * fc + 3]);
+      st.acc[fsi][fsj][fe] = __builtin_fmaf(st.T[0], s, st.acc[fsi][fsj][fe]);
+      st.acc[fsi][fsj][fe + 1] = __builtin_fmaf(st.T[1], s, st.acc[fsi][fsj][fe + 1]);
+      pin(st.acc[fsi][fsj][fe], st.acc[fsi][fsj][fe + 1]);
     }
     __builtin_amdgcn_sched_barrier(0);   // FMAs before converts
-#pragma unroll
-    for (int i = 0; i < 4; ++i) st.T[i] = (float)st.P[(u - 1) & 1][4 * g + i];
-    pin(st.T[0], st.T[1], st.T[2], st.T[3]);
+    st.T[0] = (float)st.P[(u - 1) & 1][n >> 1][2 * (n & 1)];
+    st.T[1] = (float)st.P[(u - 1) & 1][n >> 1][2 * (n & 1) + 1];
+    pin(st.T[0], st.T[1]);
     __builtin_amdgcn_sched_barrier(0);
   }
 }
@@ -227,21 +239,19 @@ __device__ __forceinline__ void run_units_range(WaveState<G>& st, const int8_t* 
 // Folds the last two units of the last item (scales sp) into the accumulators.
 template <class G>
 __device__ __forceinline__ void drain(WaveState<G>& st, const float (&sp)[G::kSP]) {
-  constexpr int kLastSi = G::kSI - 1, kSJ = G::kSJ;
+  constexpr int kLastSi = G::kSI - 1, kSJ = G::kSJ, kP = (G::kUnits - 1) & 1;
 #pragma unroll
-  for (int g = 0; g < 4; ++g) {
-    const int fsj = g ? kSJ - 1 : kSJ - 2, fc = g ? g - 1 : 3;
-    const float s = sp[G::kSP == 1 ? 0 : (g ? 1 : 0)];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      st.acc[kLastSi][fsj][4 * fc + i] = __builtin_fmaf(st.T[i], s, st.acc[kLastSi][fsj][4 * fc + i]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) st.T[i] = (float)st.P[(G::kUnits - 1) & 1][4 * g + i];
+  for (int n = 0; n < 8; ++n) {
+    const int fsj = n ? kSJ - 1 : kSJ - 2, fe = n ? 2 * (n - 1) : 14;
+    const float s = sp[G::kSP == 1 ? 0 : (n ? 1 : 0)];
+    st.acc[kLastSi][fsj][fe] = __builtin_fmaf(st.T[0], s, st.acc[kLastSi][fsj][fe]);
+    st.acc[kLastSi][fsj][fe + 1] = __builtin_fmaf(st.T[1], s, st.acc[kLastSi][fsj][fe + 1]);
+    st.T[0] = (float)st.P[kP][n >> 1][2 * (n & 1)];
+    st.T[1] = (float)st.P[kP][n >> 1][2 * (n & 1) + 1];
   }
   const float s = sp[G::kSP - 1];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-    st.acc[kLastSi][kSJ - 1][12 + i] = __builtin_fmaf(st.T[i], s, st.acc[kLastSi][kSJ - 1][12 + i]);
+  st.acc[kLastSi][kSJ - 1][14] = __builtin_fmaf(st.T[0], s, st.acc[kLastSi][kSJ - 1][14]);
+  st.acc[kLastSi][kSJ - 1][15] = __builtin_fmaf(st.T[1], s, st.acc[kLastSi][kSJ - 1][15]);
 }
 
 // Scalars of one k-block: residual slots and scales of the tile's A blocks, scales of the (up
@@ -389,17 +399,18 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
     __builtin_amdgcn_s_waitcnt(0x0F70);    // vmcnt(0): this wave's direct-to-LDS loads landed
     __syncthreads();
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      st.aq[0][g] = lds_frag(a_ring, 2 * h, g, lane);
+    for (int i = 0; i < 4; ++i) {
+      st.aq[0][i >> 1][i & 1] = lds_frag(a_ring, 2 * h, i >> 1, i & 1, lane);
 #pragma unroll
       for (int j = 0; j < kSJ; ++j) {
         const int cg = kSJ * c + j;
-        st.bq[j][g] = lds_frag(b_ring + (cg >> 2) * kBlockBytes, cg & 3, g, lane);
+        st.bq[j][i >> 1][i & 1] =
+            lds_frag(b_ring + (cg >> 2) * kBlockBytes, cg & 3, i >> 1, i & 1, lane);
       }
     }
-    st.P[1] = v16i{0};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) st.T[i] = 0.0f;
+    for (int qd = 0; qd < 4; ++qd) st.P[1][qd] = v4i{0, 0, 0, 0};
+    st.T[0] = st.T[1] = 0.0f;
     float sp[G::kSP];                      // scales of the previous item's last two units
 #pragma unroll
     for (int i = 0; i < G::kSP; ++i) sp[i] = 0.0f;
@@ -467,10 +478,10 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
     drain<G>(st, sp);
   }
 
-  // ---- epilogue.  The MFMA result layout (lane = column, registers = rows) would give 64-byte
+  // ---- epilogue.  The MFMA result layout (lane = column, registers = rows) would give 32-byte
   // global stores; instead each wavefront transposes its tile through a private LDS patch
-  // (32 rows x 32*kSJ columns of FP32 at a time, row pitch + 8 floats: conflict-free both
-  // ways) and writes whole row segments with 16-byte stores.
+  // (32 rows x 32*kSJ columns of FP32 at a time, row pitch + 4 floats) and writes whole row
+  // segments with 16-byte stores.
   __syncthreads();   // every wavefront is done reading the operand rings
   float* const stg = reinterpret_cast<float*>(lds + w * G::kStageBytesPerWave);
   const int col0 = jb_first * kBlock + c * G::kStageCols;   // first column of this wave's tile
@@ -481,10 +492,10 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
 #pragma unroll
     for (int sj = 0; sj < kSJ; ++sj)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int rl = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const int cl = sj * 32 + (lane & 31);
-        stg[rl * G::kStagePitch + cl] = bad ? __int_as_float(0x7FC00000) : st.acc[si][sj][r];
+      for (int e = 0; e < 16; ++e) {
+        const int rl = 16 * (e >> 3) + 4 * (lane >> 4) + (e & 3);
+        const int cl = sj * 32 + 16 * ((e >> 2) & 1) + (lane & 15);
+        stg[rl * G::kStagePitch + cl] = bad ? __int_as_float(0x7FC00000) : st.acc[si][sj][e];
       }
     const int row0 = (ib_first + (si >> 1)) * kBlock + h * 64 + (si & 1) * 32;
     if (p.out_bf16) {
