@@ -175,8 +175,6 @@ __device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, 
   };
 #pragma unroll
   for (int n = 0; n < 8; ++n) {
-    constexpr int kDummy = 0;
-    (void)kDummy;
     const int ks = n >> 2, rh = (n >> 1) & 1, ch = n & 1, q = 2 * rh + ch;
     {
       const v4i z = {0, 0, 0, 0};

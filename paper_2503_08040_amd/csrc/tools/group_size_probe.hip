@@ -13,7 +13,9 @@
 //       Eq. (1)), issued between the MFMAs of the next group;
 //   int8 without dequantization: the same MFMAs alone (upper bound);
 //   bf16: 8 v_mfma_f32_32x32x16_bf16 per sub-tile and 128 of K straight into the FP32
-//       accumulators (what a 16-bit fallback block would cost; needs no dequantization).
+//       accumulators (what a 16-bit fallback block would cost; needs no dequantization);
+//   int8 with v_mfma_i32_16x16x64_i8 (8 per step), without and with the group-128
+//       dequantization: the instruction shape the library's GEMM uses.
 // Prints one JSON line with the time per (32 x 32 x 128) sub-tile step and the chip-wide rate.
 // Measurement support only; not on the product path.
 #include <hip/hip_runtime.h>
@@ -88,6 +90,66 @@ __global__ __launch_bounds__(kThreads, 2) void int8_loop(const v4i* in, float* o
     for (int i = 0; i < 16; ++i) r += acc[u][i];
 #pragma unroll
   for (int i = 0; i < 16; ++i) r += (float)(P[0][i] + P[1][i]);
+  out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+}
+
+// The instruction shape the library's GEMM uses: 8 v_mfma_i32_16x16x64_i8 per sub-tile step (four
+// 16 x 16 quadrants x two halves of K = 128), group 128, 2 FMAs + 2 converts after every MFMA.
+template <bool kDequant>
+__global__ __launch_bounds__(kThreads, 2) void int8_16x16_loop(const v4i* in, float* out, float s) {
+  v4i a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    a[i] = in[(i * 2) * kThreads + threadIdx.x];
+    b[i] = in[(i * 2 + 1) * kThreads + threadIdx.x];
+  }
+  float acc[kTiles][16];
+#pragma unroll
+  for (int u = 0; u < kTiles; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[u][i] = 0.0f;
+  v4i P[2][4];
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) P[c][q] = v4i{0, 0, 0, 0};
+  asm volatile("" : "+v"(s));
+
+  for (int it = 0; it < kSteps; ++it) {
+#pragma unroll
+    for (int u = 0; u < kTiles; ++u) {
+      const int cur = u & 1;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {
+        const int ks = n >> 2, q = n & 3;
+        const v4i z = {0, 0, 0, 0};
+        P[cur][q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[(2 * ks + (q >> 1)) & 3], b[(u + n) & 3],
+                                                          ks ? P[cur][q] : z, 0, 0, 0);
+        asm volatile("" : "+v"(P[cur][q]));
+        __builtin_amdgcn_sched_barrier(0);
+        if (kDequant) {
+          const int pu = (u + kTiles - 1) % kTiles;
+#pragma unroll
+          for (int i = 0; i < 2; ++i) {
+            const int e = 2 * n + i;
+            acc[pu][e] = __builtin_fmaf((float)P[cur ^ 1][e >> 2][e & 3], s, acc[pu][e]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    }
+  }
+  float r = 0;
+#pragma unroll
+  for (int u = 0; u < kTiles; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r += acc[u][i];
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r += (float)P[c][q][i];
   out[blockIdx.x * blockDim.x + threadIdx.x] = r;
 }
 
@@ -178,19 +240,21 @@ int main() {
 
   const dim3 grid(cus), block(kThreads);
   const float s = 1e-12f;
-  double ms[5];
+  double ms[7];
   if (time_mode([&] { hipLaunchKernelGGL((int8_loop<4, false>), grid, block, 0, 0, in8, out, s); }, &ms[0])) return 1;
   if (time_mode([&] { hipLaunchKernelGGL((int8_loop<4, true>), grid, block, 0, 0, in8, out, s); }, &ms[1])) return 1;
   if (time_mode([&] { hipLaunchKernelGGL((int8_loop<2, true>), grid, block, 0, 0, in8, out, s); }, &ms[2])) return 1;
   if (time_mode([&] { hipLaunchKernelGGL((int8_loop<1, true>), grid, block, 0, 0, in8, out, s); }, &ms[3])) return 1;
   if (time_mode([&] { hipLaunchKernelGGL(bf16_loop, grid, block, 0, 0, in16, out); }, &ms[4])) return 1;
+  if (time_mode([&] { hipLaunchKernelGGL((int8_16x16_loop<false>), grid, block, 0, 0, in8, out, s); }, &ms[5])) return 1;
+  if (time_mode([&] { hipLaunchKernelGGL((int8_16x16_loop<true>), grid, block, 0, 0, in8, out, s); }, &ms[6])) return 1;
 
   // one sub-tile step = 32 x 32 x 128 multiply-accumulates; per launch and wavefront: kTiles * kSteps
   const double steps = (double)kTiles * kSteps, waves = (double)cus * (kThreads / 64);
-  const char* names[5] = {"int8_no_dequant", "int8_group128", "int8_group64", "int8_group32",
-                          "bf16_direct"};
+  const char* names[7] = {"int8_no_dequant", "int8_group128", "int8_group64", "int8_group32",
+                          "bf16_direct", "int8_16x16x64_no_dequant", "int8_16x16x64_group128"};
   printf("{\"compute_units\": %d", cus);
-  for (int m = 0; m < 5; ++m) {
+  for (int m = 0; m < 7; ++m) {
     const double ns_step = ms[m] * 1e6 / steps;                 // per wavefront, 2 wavefronts share a SIMD
     const double tops = steps * waves * 2.0 * 32 * 32 * 128 / (ms[m] * 1e-3) / 1e12;
     printf(", \"%s\": {\"ns_per_subtile_step\": %.2f, \"tops\": %.1f}", names[m], ns_step, tops);
