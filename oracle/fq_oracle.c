@@ -53,6 +53,7 @@
 #include <math.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <stdlib.h>
 #include <string.h>
 
 #define FQO_CRIT_NONE 0      /* u == 0 everywhere: plain block INT8, Eq. (1) */
@@ -517,6 +518,69 @@ int fqo_glu_backward(const uint16_t *dy_bf16, long ld_dy, const uint8_t *packed1
       dx2_bf16[(size_t)r * ldo + c] = f64_to_bf16_rne(dy * silu);
       dx1_bf16[(size_t)r * ldo + c] = f64_to_bf16_rne(dy * x2 * dsilu);
     }
+  return 0;
+}
+
+/*
+ * RMS normalization y = x * rstd * w, rstd = 1 / sqrt(mean(x^2) + eps) per row, as a non-linear
+ * layer of Sec. 5.2: bf16 input, gain and output; what it keeps for the backward pass is the
+ * INT10 1 x 128 context of x (fqo_ctx_quantize) and rstd per row (binary32).  Evaluated in
+ * binary64, each result rounded once.
+ */
+int fqo_rmsnorm_forward(const uint16_t *x_bf16, const uint16_t *w_bf16, int rows, int cols,
+                        long ld, double eps, uint16_t *y_bf16, long ldy, float *rstd) {
+  if (!x_bf16 || !w_bf16 || !y_bf16 || !rstd) return -1;
+  if (rows < 0 || cols < 1 || ld < cols || ldy < cols) return -2;
+  for (int r = 0; r < rows; ++r) {
+    double ss = 0.0;
+    for (int c = 0; c < cols; ++c) {
+      double x = (double)bf16_to_f32(x_bf16[(size_t)r * ld + c]);
+      ss += x * x;
+    }
+    double rs = 1.0 / sqrt(ss / (double)cols + eps);
+    rstd[r] = (float)rs;
+    for (int c = 0; c < cols; ++c) {
+      double x = (double)bf16_to_f32(x_bf16[(size_t)r * ld + c]);
+      double w = (double)bf16_to_f32(w_bf16[c]);
+      y_bf16[(size_t)r * ldy + c] = f64_to_bf16_rne(x * rs * w);
+    }
+  }
+  return 0;
+}
+
+/*
+ * Backward of the RMS normalization from dy, the INT10 context of x, the stored rstd and the
+ * gain: with x~ the dequantized context, xh = x~ * rstd, g = dy * w,
+ *   dx = rstd * (g - xh * mean(g * xh)),     dw[c] = sum over rows of dy * xh.
+ * Binary64 evaluation; dx rounded once to bf16, dw to binary32.
+ */
+int fqo_rmsnorm_backward(const uint16_t *dy_bf16, long ld_dy, const uint8_t *packed,
+                         const float *scales, const float *rstd, const uint16_t *w_bf16,
+                         int rows, int cols, uint16_t *dx_bf16, long ldo, float *dw) {
+  if (!dy_bf16 || !packed || !scales || !rstd || !w_bf16 || !dx_bf16 || !dw) return -1;
+  if (rows < 0 || cols < 1 || ld_dy < cols || ldo < cols) return -2;
+  const int ng = (cols + 127) / 128;
+  double *acc = (double *)calloc((size_t)cols, sizeof(double));
+  if (!acc) return -7;
+  for (int r = 0; r < rows; ++r) {
+    const double rs = (double)rstd[r];
+    double m = 0.0;
+    for (int c = 0; c < cols; ++c) {
+      double xh = (double)ctx_value(packed, scales, ng, r, c) * rs;
+      double g = (double)bf16_to_f32(dy_bf16[(size_t)r * ld_dy + c]) * (double)bf16_to_f32(w_bf16[c]);
+      m += g * xh;
+    }
+    m /= (double)cols;
+    for (int c = 0; c < cols; ++c) {
+      double xh = (double)ctx_value(packed, scales, ng, r, c) * rs;
+      double dy = (double)bf16_to_f32(dy_bf16[(size_t)r * ld_dy + c]);
+      double g = dy * (double)bf16_to_f32(w_bf16[c]);
+      dx_bf16[(size_t)r * ldo + c] = f64_to_bf16_rne(rs * (g - xh * m));
+      acc[c] += dy * xh;
+    }
+  }
+  for (int c = 0; c < cols; ++c) dw[c] = (float)acc[c];
+  free(acc);
   return 0;
 }
 

@@ -57,6 +57,12 @@ def lib():
         _lib.fqo_glu_backward.restype = C.c_int
         _lib.fqo_glu_backward.argtypes = [C.c_void_p, C.c_long] + [C.c_void_p] * 4 + \
                                          [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_long]
+        _lib.fqo_rmsnorm_forward.restype = C.c_int
+        _lib.fqo_rmsnorm_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_long,
+                                             C.c_double, C.c_void_p, C.c_long, C.c_void_p]
+        _lib.fqo_rmsnorm_backward.restype = C.c_int
+        _lib.fqo_rmsnorm_backward.argtypes = [C.c_void_p, C.c_long] + [C.c_void_p] * 4 + \
+                                             [C.c_int, C.c_int, C.c_void_p, C.c_long, C.c_void_p]
         _lib.fqo_threshold_update.restype = C.c_float
         _lib.fqo_threshold_update.argtypes = [C.c_float, C.c_int, C.c_int, C.c_float, C.c_float,
                                               C.c_float]
@@ -228,3 +234,35 @@ def glu_backward(dy_bf16: np.ndarray, ctx1, ctx2):
     if rc != 0:
         raise RuntimeError(f"fqo_glu_backward failed: {rc}")
     return dx1, dx2
+
+
+def rmsnorm_forward(x_bf16: np.ndarray, w_bf16: np.ndarray, eps: float):
+    """y = x * rstd * w per row (non-linear layer of Sec. 5.2): returns (y bf16 bits, rstd float32
+    [rows], INT10 context of x as a (packed, scales) pair)."""
+    x = np.ascontiguousarray(x_bf16)
+    w = np.ascontiguousarray(w_bf16)
+    rows, cols = x.shape
+    assert w.shape == (cols,) and x.dtype == w.dtype == np.uint16
+    y = np.zeros((rows, cols), np.uint16)
+    rstd = np.zeros(rows, np.float32)
+    rc = lib().fqo_rmsnorm_forward(x.ctypes.data, w.ctypes.data, rows, cols, cols, float(eps),
+                                   y.ctypes.data, cols, rstd.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"fqo_rmsnorm_forward failed: {rc}")
+    return y, rstd, ctx_quantize(x)
+
+
+def rmsnorm_backward(dy_bf16: np.ndarray, ctx, rstd: np.ndarray, w_bf16: np.ndarray):
+    """(dx bf16 bits, dw float32 [cols]) from dy, the INT10 context of x, rstd and the gain."""
+    dy = np.ascontiguousarray(dy_bf16)
+    w = np.ascontiguousarray(w_bf16)
+    rs = np.ascontiguousarray(rstd, dtype=np.float32)
+    rows, cols = dy.shape
+    dx = np.zeros((rows, cols), np.uint16)
+    dw = np.zeros(cols, np.float32)
+    rc = lib().fqo_rmsnorm_backward(dy.ctypes.data, cols, ctx[0].ctypes.data, ctx[1].ctypes.data,
+                                    rs.ctypes.data, w.ctypes.data, rows, cols, dx.ctypes.data, cols,
+                                    dw.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"fqo_rmsnorm_backward failed: {rc}")
+    return dx, dw
