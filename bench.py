@@ -199,7 +199,26 @@ def context(args):
                                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                     "frac": round(nbytes / ms_d / 1e6 / HBM_PEAK_GBS, 4)},
             "bf16_copy_gbs": round(4.0 * rows * cols / ms_c / 1e6, 1),
-            "glu": glu_times(x)}
+            "glu": glu_times(x), "rmsnorm": rmsnorm_times(x)}
+
+
+def rmsnorm_times(x):
+    """RMS normalization forward / backward with a fused INT10 context on a tensor of x's shape:
+    algorithmic bytes per element forward 2 (x) + 2 (y) + 1.28 (context) = 5.28, backward
+    2 (dy) + 1.28 + 2 (dx) = 5.28 (the gain, rstd and the dw partial sums are negligible; the
+    backward pass as built reads dy and the context twice, 8.56 in all)."""
+    import torch
+    import paper_2503_08040_amd as fq
+    rows, cols = x.shape
+    w = torch.ones(cols, dtype=torch.bfloat16, device=x.device)
+    y, rstd, ctx = fq.fq_rmsnorm_forward(x, w, 1e-5)
+    ms_f = _time_loop(lambda: fq.fq_rmsnorm_forward(x, w, 1e-5), 1.0, 50)
+    ms_b = _time_loop(lambda: fq.fq_rmsnorm_backward(y, ctx, rstd, w, n_parts=256), 1.0, 50)
+    nbytes = 4.0 * rows * cols + ctx[0].numel() + 4.0 * ctx[1].numel()
+    return {"ms_forward": round(ms_f, 5), "ms_backward": round(ms_b, 5),
+            "forward_gbs": round(nbytes / ms_f / 1e6, 1), "backward_gbs": round(nbytes / ms_b / 1e6, 1),
+            "forward_frac_of_hbm_peak": round(nbytes / ms_f / 1e6 / HBM_PEAK_GBS, 4),
+            "backward_frac_of_hbm_peak": round(nbytes / ms_b / 1e6 / HBM_PEAK_GBS, 4)}
 
 
 def glu_times(x):

@@ -244,6 +244,35 @@ fq_status fq_glu_backward(const void *dy_bf16, int64_t ld_dy, const uint8_t *ctx
                           void *dx2_bf16, int64_t ldo, void *hip_stream);
 
 /*
+ * RMS normalization y = x * rstd * w, rstd = 1 / sqrt(mean(x^2) + eps) per row, as a non-linear
+ * layer of Sec. 5.2: bf16 input x [rows, ld], gain w [cols] and output y [rows, ldy]; the same
+ * pass writes what the backward pass needs: the INT10 context of x (exactly what
+ * fq_ctx_quantize would write) and rstd [rows] (float).  Binary32 arithmetic (the sum of squares
+ * in unspecified order, then correctly rounded division, square root and division): rstd is
+ * within a few binary32 ulps of the exact value and y within one bf16 step of the correctly
+ * rounded one.  cols >= 1.  Errors and layouts as fq_ctx_quantize.
+ */
+fq_status fq_rmsnorm_forward(const void *x_bf16, const void *w_bf16, int32_t rows, int32_t cols,
+                             int64_t ld, float eps, void *y_bf16, int64_t ldy,
+                             uint8_t *ctx_packed, float *ctx_scales, float *rstd,
+                             void *hip_stream);
+
+/*
+ * Backward of fq_rmsnorm_forward with the context dequantized on the fly (Sec. 5.3): with
+ * x~ = a*q, xh = x~ * rstd, g = dy * w,
+ *   dx = rstd * (g - xh * mean(g * xh))   [rows, ldo] bf16,
+ *   dw[c] = sum over rows of dy * xh      [cols] float.
+ * Three kernels: the row means (one workgroup per row), dx together with partial column sums of
+ * dy * xh (rows part, part + n_parts, ... per part; 1 <= n_parts <= 65535, 256 is a good choice),
+ * and the sum of the parts in a fixed order, so dw is deterministic for a given n_parts.
+ * workspace: device, float [n_parts * cols + rows], overwritten.  rows == 0 writes dw = 0.
+ */
+fq_status fq_rmsnorm_backward(const void *dy_bf16, int64_t ld_dy, const uint8_t *ctx_packed,
+                              const float *ctx_scales, const float *rstd, const void *w_bf16,
+                              int32_t rows, int32_t cols, void *dx_bf16, int64_t ldo, float *dw,
+                              float *workspace, int32_t n_parts, void *hip_stream);
+
+/*
  * Fallback block GEMM (Alg. 1).  For every output tile, k-blocks ascending:
  *   C += float(P) * (a^A_ik * a^B_kj),  P the exact INT32 product of the code blocks,
  *   and, if u(i,k) = 1,  C += float(P~) * (a~^A_ik * a^B_kj)  with the residual

@@ -26,7 +26,8 @@ EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr
            "fq_threshold_update", "fq_gemm",
            "fq_gemm_debug_partials", "fq_codes_to_rowmajor", "fq_qtensor_check",
            "fq_status_string", "fq_ctx_packed_bytes", "fq_ctx_scales_bytes", "fq_ctx_quantize",
-           "fq_ctx_dequantize", "fq_gemm_tile_plan", "fq_glu_forward", "fq_glu_backward"]
+           "fq_ctx_dequantize", "fq_gemm_tile_plan", "fq_glu_forward", "fq_glu_backward", "fq_rmsnorm_forward",
+           "fq_rmsnorm_backward"]
 
 
 class fq_qtensor(C.Structure):
@@ -99,6 +100,14 @@ def lib():
         L.fq_glu_backward.argtypes = [C.c_void_p, C.c_int64] + [C.c_void_p] * 4 + \
                                      [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64,
                                       C.c_void_p]
+        L.fq_rmsnorm_forward.restype = C.c_int
+        L.fq_rmsnorm_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
+                                         C.c_float, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p]
+        L.fq_rmsnorm_backward.restype = C.c_int
+        L.fq_rmsnorm_backward.argtypes = [C.c_void_p, C.c_int64] + [C.c_void_p] * 4 + \
+                                         [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
+                                          C.c_void_p, C.c_int32, C.c_void_p]
         L.fq_gemm_tile_plan.restype = C.c_int
         L.fq_gemm_tile_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         _lib = L
@@ -352,3 +361,40 @@ def fq_glu_backward(dy, ctx1, ctx2, stream=None):
                                  rows, cols, C.c_void_p(dx1.data_ptr()), C.c_void_p(dx2.data_ptr()),
                                  _pitch(dx1), _stream_ptr(stream)), "fq_glu_backward")
     return dx1, dx2
+
+
+def fq_rmsnorm_forward(x, w, eps, stream=None):
+    """y = x * rstd * w per row with the INT10 context of x and rstd written in the same pass.
+    Returns (y bf16, rstd float32 [rows], (packed, scales))."""
+    import torch
+    assert x.dtype == w.dtype == torch.bfloat16 and x.dim() == 2 and w.shape == (x.shape[1],)
+    assert w.is_contiguous()
+    rows, cols = x.shape
+    ng = -(-cols // FQ_CTX_GROUP)
+    y = torch.empty((rows, cols), dtype=torch.bfloat16, device=x.device)
+    rstd = torch.empty((rows,), dtype=torch.float32, device=x.device)
+    packed = torch.empty((rows, ng, FQ_CTX_GROUP_BYTES), dtype=torch.uint8, device=x.device)
+    scales = torch.empty((rows, ng), dtype=torch.float32, device=x.device)
+    _check(lib().fq_rmsnorm_forward(C.c_void_p(x.data_ptr()), C.c_void_p(w.data_ptr()), rows, cols,
+                                    _pitch(x), C.c_float(eps), C.c_void_p(y.data_ptr()), _pitch(y),
+                                    C.c_void_p(packed.data_ptr()), C.c_void_p(scales.data_ptr()),
+                                    C.c_void_p(rstd.data_ptr()), _stream_ptr(stream)),
+           "fq_rmsnorm_forward")
+    return y, rstd, (packed, scales)
+
+
+def fq_rmsnorm_backward(dy, ctx, rstd, w, n_parts=256, stream=None):
+    """(dx bf16, dw float32 [cols]) from dy, the context and rstd of fq_rmsnorm_forward, and w."""
+    import torch
+    assert dy.dtype == w.dtype == torch.bfloat16 and dy.dim() == 2 and w.is_contiguous()
+    rows, cols = dy.shape
+    dx = torch.empty((rows, cols), dtype=torch.bfloat16, device=dy.device)
+    dw = torch.empty((cols,), dtype=torch.float32, device=dy.device)
+    parts = torch.empty((n_parts * cols + rows,), dtype=torch.float32, device=dy.device)
+    _check(lib().fq_rmsnorm_backward(C.c_void_p(dy.data_ptr()), _pitch(dy),
+                                     C.c_void_p(ctx[0].data_ptr()), C.c_void_p(ctx[1].data_ptr()),
+                                     C.c_void_p(rstd.data_ptr()), C.c_void_p(w.data_ptr()), rows, cols,
+                                     C.c_void_p(dx.data_ptr()), _pitch(dx), C.c_void_p(dw.data_ptr()),
+                                     C.c_void_p(parts.data_ptr()), int(n_parts), _stream_ptr(stream)),
+           "fq_rmsnorm_backward")
+    return dx, dw

@@ -293,6 +293,54 @@ fq_status fq_glu_backward(const void* dy_bf16, int64_t ld_dy, const uint8_t* ctx
   return FQ_OK;
 }
 
+fq_status fq_rmsnorm_forward(const void* x_bf16, const void* w_bf16, int32_t rows, int32_t cols,
+                             int64_t ld, float eps, void* y_bf16, int64_t ldy, uint8_t* ctx_packed,
+                             float* ctx_scales, float* rstd, void* hip_stream) {
+  const int64_t n = ctx_groups(rows, cols);
+  if (n < 0 || cols < 1 || ld < cols || ldy < cols) return FQ_ERR_SHAPE;
+  if (rows == 0) return FQ_OK;
+  if (!x_bf16 || !w_bf16 || !y_bf16 || !ctx_packed || !ctx_scales || !rstd) return FQ_ERR_NULL;
+  if ((uintptr_t)ctx_packed & 3) return FQ_ERR_SHAPE;
+  fq::RmsParams p{};
+  p.x = static_cast<const uint16_t*>(x_bf16); p.ld = ld;
+  p.w = static_cast<const uint16_t*>(w_bf16);
+  p.y = static_cast<uint16_t*>(y_bf16); p.ldy = ldy;
+  p.rstd = rstd; p.eps = eps; p.packed = ctx_packed; p.scales = ctx_scales;
+  p.rows = rows; p.cols = cols; p.ng = (int)ceil_div(cols, FQ_CTX_GROUP);
+  p.vec_ok = bf16_vec_ok(x_bf16, ld) && bf16_vec_ok(y_bf16, ldy);
+  p.vec_w = ((uintptr_t)w_bf16 & 15) == 0;
+  if (fq::launch_rmsnorm(p, false, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return FQ_ERR_HIP;
+  return FQ_OK;
+}
+
+fq_status fq_rmsnorm_backward(const void* dy_bf16, int64_t ld_dy, const uint8_t* ctx_packed,
+                              const float* ctx_scales, const float* rstd, const void* w_bf16,
+                              int32_t rows, int32_t cols, void* dx_bf16, int64_t ldo, float* dw,
+                              float* workspace, int32_t n_parts, void* hip_stream) {
+  const int64_t n = ctx_groups(rows, cols);
+  if (n < 0 || cols < 1 || ld_dy < cols || ldo < cols) return FQ_ERR_SHAPE;
+  if (n_parts < 1 || n_parts > 65535) return FQ_ERR_SHAPE;
+  if (!dw || !workspace) return FQ_ERR_NULL;
+  if (rows > 0 && (!dy_bf16 || !dx_bf16 || !ctx_packed || !ctx_scales || !rstd || !w_bf16))
+    return FQ_ERR_NULL;
+  if ((uintptr_t)ctx_packed & 3) return FQ_ERR_SHAPE;
+  fq::RmsParams p{};
+  p.dy = static_cast<const uint16_t*>(dy_bf16); p.ld_dy = ld_dy;
+  p.dx = static_cast<uint16_t*>(dx_bf16); p.ldo = ldo;
+  p.w = static_cast<const uint16_t*>(w_bf16);
+  p.rstd = const_cast<float*>(rstd); p.dw = dw; p.n_parts = n_parts;
+  p.dw_parts = workspace; p.row_mean = workspace + (size_t)n_parts * cols;
+  p.packed = const_cast<uint8_t*>(ctx_packed); p.scales = const_cast<float*>(ctx_scales);
+  p.rows = rows; p.cols = cols; p.ng = (int)ceil_div(cols, FQ_CTX_GROUP);
+  p.vec_ok = bf16_vec_ok(dy_bf16, ld_dy) && bf16_vec_ok(dx_bf16, ldo);
+  p.vec_w = ((uintptr_t)w_bf16 & 15) == 0;
+  // with no rows the partial sums are all zero: the kernels still run so that dw is written
+  if (fq::launch_rmsnorm(p, true, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+    return FQ_ERR_HIP;
+  return FQ_OK;
+}
+
 fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,
                   int64_t ldc, void* hip_stream) {
   fq::GemmParams g;

@@ -202,7 +202,176 @@ __global__ __launch_bounds__(kCtxThreads) void glu_backward_kernel(GluParams p) 
   store16(p.dx2 + q.r * p.ldo + q.c0, p.vec_ok, q.c0, p.cols, d2);
 }
 
+// ---- RMS normalization with a fused INT10 context --------------------------------------------
+// One 256-thread workgroup walks a row in chunks of 32 groups (4096 columns): thread t is lane
+// t % 8 of group t / 8 of the chunk, the same team layout as above.
+constexpr int kRowChunkGroups = kCtxThreads / kLanesPerGroup;   // 32
+constexpr int kRowChunkCols = kRowChunkGroups * kCtxGroup;      // 4096
+constexpr int kRmsMaxChunks = 4;                                // forward keeps rows of up to 4 chunks in registers
+
+__device__ inline LanePos row_pos(int64_t r, int chunk, int ng) {
+  LanePos q;
+  const int j = chunk * kRowChunkGroups + (int)(threadIdx.x / kLanesPerGroup);
+  q.s = (int)(threadIdx.x % kLanesPerGroup);
+  q.live = j < ng;
+  q.r = r;
+  q.g = r * ng + (q.live ? j : 0);
+  q.c0 = (q.live ? j : 0) * kCtxGroup + q.s * kValsPerLane;
+  return q;
+}
+
+// sum over the workgroup; every thread gets the result.  red: 4 floats of LDS.
+__device__ inline float block_sum(float v, float* red) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  __syncthreads();  // red may still be read from a previous call
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// y = x * rstd * w, rstd = 1 / sqrt(mean(x^2) + eps); also writes rstd and the INT10 context of x.
+// kCache: the row (at most kRmsMaxChunks chunks) stays in registers between the two passes;
+// otherwise it is read a second time (cache-hot).
+template <bool kCache>
+__global__ __launch_bounds__(kCtxThreads) void rmsnorm_forward_kernel(RmsParams p) {
+  __shared__ float red[4];
+  const int64_t r = blockIdx.x;
+  const int chunks = (p.ng + kRowChunkGroups - 1) / kRowChunkGroups;
+  float xc[kCache ? kRmsMaxChunks : 1][kValsPerLane];
+  float ss = 0.0f;
+  if (kCache) {
+#pragma unroll
+    for (int ch = 0; ch < kRmsMaxChunks; ++ch) {
+      const LanePos q = row_pos(r, ch, p.ng);
+      load16(p.x + r * p.ld + q.c0, q.live && ch < chunks, p.vec_ok, q.c0, p.cols, xc[ch]);
+#pragma unroll
+      for (int i = 0; i < kValsPerLane; ++i) ss = __builtin_fmaf(xc[ch][i], xc[ch][i], ss);
+    }
+  } else {
+    for (int ch = 0; ch < chunks; ++ch) {
+      const LanePos q = row_pos(r, ch, p.ng);
+      load16(p.x + r * p.ld + q.c0, q.live, p.vec_ok, q.c0, p.cols, xc[0]);
+#pragma unroll
+      for (int i = 0; i < kValsPerLane; ++i) ss = __builtin_fmaf(xc[0][i], xc[0][i], ss);
+    }
+  }
+  ss = block_sum(ss, red);
+  const float rstd = __fdiv_rn(1.0f, __fsqrt_rn(__fdiv_rn(ss, (float)p.cols) + p.eps));
+  if (threadIdx.x == 0) p.rstd[r] = rstd;
+  auto finish = [&](int ch, const float (&x)[kValsPerLane]) {
+    const LanePos q = row_pos(r, ch, p.ng);
+    float w[kValsPerLane], y[kValsPerLane];
+    load16(p.w + q.c0, q.live, p.vec_w, q.c0, p.cols, w);
+#pragma unroll
+    for (int i = 0; i < kValsPerLane; ++i) y[i] = x[i] * rstd * w[i];
+    if (q.live && q.c0 < p.cols) store16(p.y + r * p.ldy + q.c0, p.vec_ok, q.c0, p.cols, y);
+    quantize_store(x, q, p.packed, p.scales);
+  };
+  if (kCache) {
+#pragma unroll
+    for (int ch = 0; ch < kRmsMaxChunks; ++ch)
+      if (ch < chunks) finish(ch, xc[ch]);      // uniform over the workgroup
+  } else {
+    for (int ch = 0; ch < chunks; ++ch) {
+      const LanePos q = row_pos(r, ch, p.ng);
+      load16(p.x + r * p.ld + q.c0, q.live, p.vec_ok, q.c0, p.cols, xc[0]);
+      finish(ch, xc[0]);
+    }
+  }
+}
+
+// First backward kernel, one workgroup per row: m[r] = mean over the row of g * xh, with
+// xh = x~ * rstd (x~ dequantized from the context) and g = dy * w.
+__global__ __launch_bounds__(kCtxThreads) void rmsnorm_rowdot_kernel(RmsParams p) {
+  __shared__ float red[4];
+  const int64_t r = blockIdx.x;
+  const int chunks = (p.ng + kRowChunkGroups - 1) / kRowChunkGroups;
+  const float rstd = p.rstd[r];
+  float m = 0.0f;
+  for (int ch = 0; ch < chunks; ++ch) {
+    const LanePos q = row_pos(r, ch, p.ng);
+    if (!q.live || q.c0 >= p.cols) continue;
+    float dy[kValsPerLane], w[kValsPerLane], xq[kValsPerLane];
+    load16(p.dy + r * p.ld_dy + q.c0, true, p.vec_ok, q.c0, p.cols, dy);
+    load16(p.w + q.c0, true, p.vec_w, q.c0, p.cols, w);
+    load_dequantized(p.packed, p.scales, q, xq);
+#pragma unroll
+    for (int i = 0; i < kValsPerLane; ++i) m = __builtin_fmaf(dy[i] * w[i], xq[i] * rstd, m);
+  }
+  m = block_sum(m, red);
+  if (threadIdx.x == 0) p.row_mean[r] = __fdiv_rn(m, (float)p.cols);
+}
+
+// Second backward kernel, workgroup (chunk, part): for the rows part, part + n_parts, ... and
+// the 4096 columns of the chunk, dx = rstd * (g - xh * m[r]) and the partial column sums of
+// dy * xh over those rows.
+__global__ __launch_bounds__(kCtxThreads) void rmsnorm_dx_dw_kernel(RmsParams p) {
+  const int ch = blockIdx.x, part = blockIdx.y;
+  const LanePos q0 = row_pos(0, ch, p.ng);
+  if (!q0.live || q0.c0 >= p.cols) return;      // no reductions in this kernel: lanes may leave
+  float w[kValsPerLane], dwacc[kValsPerLane];
+  load16(p.w + q0.c0, true, p.vec_w, q0.c0, p.cols, w);
+#pragma unroll
+  for (int i = 0; i < kValsPerLane; ++i) dwacc[i] = 0.0f;
+  for (int64_t r = part; r < p.rows; r += p.n_parts) {
+    const LanePos q = row_pos(r, ch, p.ng);
+    const float rstd = p.rstd[r], m = p.row_mean[r];
+    float dy[kValsPerLane], xq[kValsPerLane], dx[kValsPerLane];
+    load16(p.dy + r * p.ld_dy + q.c0, true, p.vec_ok, q.c0, p.cols, dy);
+    load_dequantized(p.packed, p.scales, q, xq);
+#pragma unroll
+    for (int i = 0; i < kValsPerLane; ++i) {
+      const float xh = xq[i] * rstd;
+      dx[i] = rstd * (dy[i] * w[i] - xh * m);
+      dwacc[i] = __builtin_fmaf(dy[i], xh, dwacc[i]);
+    }
+    store16(p.dx + r * p.ldo + q.c0, p.vec_ok, q.c0, p.cols, dx);
+  }
+  float* dst = p.dw_parts + (int64_t)part * p.cols + q0.c0;
+#pragma unroll
+  for (int i = 0; i < kValsPerLane; ++i)
+    if (q0.c0 + i < p.cols) dst[i] = dwacc[i];
+}
+
+// dw[c] = sum of the partial sums: four interleaved slices of parts per column, each added in
+// part order, then the four slice sums in slice order (deterministic).
+__global__ __launch_bounds__(256) void rmsnorm_dw_kernel(const float* parts, int n_parts, int cols,
+                                                         float* dw) {
+  __shared__ float red[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63), k = threadIdx.x >> 6;
+  float s = 0.0f;
+  if (c < cols)
+    for (int i = k; i < n_parts; i += 4) s += parts[(int64_t)i * cols + c];
+  red[k][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (k == 0 && c < cols)
+    dw[c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
 }  // namespace
+
+hipError_t launch_rmsnorm(const RmsParams& p, bool backward, hipStream_t st) {
+  const int chunks = (p.ng + kRowChunkGroups - 1) / kRowChunkGroups;
+  if (!backward) {
+    if (p.rows == 0) return hipSuccess;
+    if (chunks <= kRmsMaxChunks)
+      hipLaunchKernelGGL(rmsnorm_forward_kernel<true>, dim3((unsigned)p.rows), dim3(kCtxThreads), 0, st, p);
+    else
+      hipLaunchKernelGGL(rmsnorm_forward_kernel<false>, dim3((unsigned)p.rows), dim3(kCtxThreads), 0, st, p);
+    return hipGetLastError();
+  }
+  // no rows: nothing is read (the other pointers may be NULL); summing zero parts writes dw = 0
+  const int n_parts = p.rows > 0 ? p.n_parts : 0;
+  if (p.rows > 0) {
+    hipLaunchKernelGGL(rmsnorm_rowdot_kernel, dim3((unsigned)p.rows), dim3(kCtxThreads), 0, st, p);
+    hipLaunchKernelGGL(rmsnorm_dx_dw_kernel, dim3((unsigned)chunks, (unsigned)p.n_parts),
+                       dim3(kCtxThreads), 0, st, p);
+  }
+  hipLaunchKernelGGL(rmsnorm_dw_kernel, dim3((unsigned)((p.cols + 63) / 64)), dim3(256), 0, st, p.dw_parts,
+                     n_parts, p.cols, p.dw);
+  return hipGetLastError();
+}
 
 hipError_t launch_glu(const GluParams& p, bool backward, hipStream_t st) {
   if (p.n_groups == 0) return hipSuccess;

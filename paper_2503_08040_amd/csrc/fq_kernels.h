@@ -93,12 +93,39 @@ struct GluParams {
   int vec_ok;          // every bf16 matrix of the call allows 16-byte accesses
 };
 
+// RMS normalization with a fused INT10 context (forward: x, w -> y, rstd, context; backward:
+// dy, context, rstd, w -> dx, dw through dw_parts [n_parts, cols]).
+struct RmsParams {
+  const uint16_t* x;   // forward input [rows, ld]
+  int64_t ld;
+  const uint16_t* w;   // gain [cols] bf16
+  uint16_t* y;
+  int64_t ldy;
+  float* rstd;         // [rows]: written by forward, read by backward
+  float eps;
+  const uint16_t* dy;
+  int64_t ld_dy;
+  uint16_t* dx;
+  int64_t ldo;
+  float* dw;           // [cols]
+  float* dw_parts;     // [n_parts, cols] workspace
+  float* row_mean;     // [rows] workspace: mean over the row of g * xh
+  int n_parts;
+  uint8_t* packed;
+  float* scales;
+  int64_t rows;
+  int cols, ng;
+  int vec_ok;          // the [rows, pitch] bf16 matrices of the call allow 16-byte accesses
+  int vec_w;           // so does w
+};
+
 hipError_t launch_quantize(const QuantParams& p, hipStream_t st);
 hipError_t launch_untile(const int8_t* tiled, int rows, int cols, int8_t* dense, hipStream_t st);
 hipError_t launch_gemm(const GemmParams& p, bool debug, hipStream_t st);
 // out = {workgroups with 2x2-block tiles, tile columns they cover, 1x3-block tile columns};
 // cus <= 0: the current device's compute units (or FQ_GEMM_CUS).
 void gemm_tile_plan(int nib, int njb, int cus, int out[3]);
+hipError_t launch_rmsnorm(const RmsParams& p, bool backward, hipStream_t st);
 hipError_t launch_glu(const GluParams& p, bool backward, hipStream_t st);
 hipError_t launch_ctx(const CtxParams& p, bool dequantize, hipStream_t st);
 
