@@ -26,7 +26,12 @@ def _matrix(rng, shape, heavy):
     return synth.to_bf16_bits(x)
 
 
-@pytest.mark.parametrize("seed", list(range(12)))
+import os
+
+N_SEEDS = int(os.environ.get("FQ_TEST_RANDOM_SEEDS", "12"))     # more seeds for an occasional longer run
+
+
+@pytest.mark.parametrize("seed", list(range(N_SEEDS)))
 def test_random_case(seed, monkeypatch):
     rng = np.random.default_rng(1000 + seed)
     op = int(rng.integers(0, 3))
