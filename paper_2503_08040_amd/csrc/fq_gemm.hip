@@ -8,21 +8,23 @@
 //
 // Shape of the kernel (differs from the paper's 128^3 CUDA tile on purpose):
 //   - workgroup = 8 wavefronts (2 per SIMD), output tile 256 x 256 = 2 x 2
-//     quantization blocks.  Wavefront (h, c) owns rows [64h, 64h+64) of BOTH
-//     i-blocks and the 64-column quarter c of the tile: 4 x 2 sub-tiles of
-//     32 x 32, 128 FP32 accumulators per lane in architectural VGPRs (the
-//     vector ALU cannot read accumulation registers, so the accumulators it
-//     updates must not live there).  A second geometry, 1 x 3 blocks
-//     (128 x 384, 2 x 3 sub-tiles per wavefront), covers the last block columns
-//     when the 2 x 2 tiles would leave the final round of the chip mostly idle;
+//     quantization blocks.  Wavefront (h, c) owns all 128 rows of i-block h and
+//     the 64-column quarter c of the tile: 4 x 2 sub-tiles of 32 x 32, 128 FP32
+//     accumulators per lane in architectural VGPRs (the vector ALU cannot read
+//     accumulation registers, so the accumulators it updates must not live
+//     there).  A second geometry, 1 x 3 blocks (128 x 384, 2 x 3 sub-tiles per
+//     wavefront), covers the last block columns when the 2 x 2 tiles would
+//     leave the final round of the chip mostly idle;
 //   - the k-loop runs over "items": the main product of k-block k and, when
 //     one of the tile's A blocks is flagged at k, a residual item right
 //     after it.  A and B operands sit in two independent double-buffered LDS
 //     rings (64 KiB each for 2 x 2): an item always brings a new A set (codes or
 //     residual codes), a new B set only when k advances, so the residual
 //     product re-uses the B blocks already on chip exactly as Alg. 1 says.
-//     Because every wavefront spans all i-blocks of the tile, a residual item
-//     loads every wavefront equally;
+//     A residual item is work only for the wavefronts whose i-block is flagged
+//     at that k: the others skip its multiplications (they still take part in
+//     staging and in the barrier), so with one of the two blocks flagged the
+//     item runs on one wavefront per SIMD and costs about 60 % of a full item;
 //   - operands reach LDS by direct global->LDS 16-byte loads (blocks are stored
 //     in operand order, see fq.h), one barrier per item;
 //   - per 32 x 32 sub-tile: 8 v_mfma_i32_16x16x64_i8 (four 16 x 16 quadrants x
@@ -122,6 +124,12 @@ struct Geo {
   static constexpr int kStageCols = 32 * kSJ;
   static constexpr int kStagePitch = kStageCols + 4;   // floats per staged row: 4 rows apart = 16 banks apart
   static constexpr int kStageBytesPerWave = 32 * kStagePitch * 4;
+  // Rows of a wavefront.  With two i-blocks per tile, wavefront half h owns all 128 rows of
+  // i-block h (so that a residual item of one flagged block is work for that half of the
+  // wavefronts only); with one i-block it owns rows [64h, 64h+64) of it.  si counts the
+  // wavefront's 32-row groups: its i-block and its row group inside that block.
+  __device__ static constexpr int a_block(int h, int /*si*/) { return kBI == 2 ? h : 0; }
+  __device__ static constexpr int a_group(int h, int si) { return kBI == 2 ? si : 2 * h + si; }
   static_assert(2 * (kASet + kBSet) <= kLdsBytes, "operand rings must fit");
   static_assert(8 * kStageBytesPerWave <= kLdsBytes, "epilogue staging must fit");
   static_assert(kBI + kBJ == 4, "8 wavefronts stage 8 half-blocks per item");
@@ -139,11 +147,11 @@ struct WaveState {
   float T[2];                      // elements converted in the previous slot, waiting for their FMA
 };
 
-// Scales of one item as the units see them: s[bi][sc] = a^A (or a~^A) of i-block bi times a^B
-// of the j-block that scale column sc lies in.
+// Scales of one item as this wavefront's units see them: s[sc] = a^A (or a~^A) of the
+// wavefront's i-block times a^B of the j-block that scale column sc lies in.
 template <class G>
 struct ItemScales {
-  float s[G::kBI][G::kSC];
+  float s[G::kSC];
 };
 
 // The k-loop is one continuous software pipeline over sub-tiles ("units": u = kSJ*si + sj).
@@ -186,12 +194,13 @@ __device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, 
       const int i = 2 * ks + ch, irh = i >> 1, iks = i & 1;
       // A operands of the next si go into the other aq buffer a whole unit before their use
       if (si + 1 < G::kSI && sj == 0 && !b_done)
-        st.aq[(si + 1) & 1][irh][iks] = lds_frag(a_cur + ((si + 1) >> 1) * kBlockBytes,
-                                                 2 * h + ((si + 1) & 1), irh, iks, lane);
+        st.aq[(si + 1) & 1][irh][iks] = lds_frag(a_cur + G::a_block(h, si + 1) * kBlockBytes,
+                                                 G::a_group(h, si + 1), irh, iks, lane);
       // the last two units (same si, odd: they use aq[1]) fetch the next item's first operands
       if (u == kUnits - 2) {
         if (b_done) st.bq[sj][ch][ks] = b_frag(sj, ch, ks);
-        else st.aq[0][irh][iks] = lds_frag(a_nxt, 2 * h, irh, iks, lane);
+        else st.aq[0][irh][iks] = lds_frag(a_nxt + G::a_block(h, 0) * kBlockBytes,
+                                           G::a_group(h, 0), irh, iks, lane);
       }
       if (u == kUnits - 1) {
         if (b_done) st.bq[sj][ch][ks] = b_frag(sj, ch, ks);
@@ -209,7 +218,7 @@ __device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, 
       const int pu = fu + kUnits;                       // unit index in the previous item
       const int fsi = prev ? kLastSi : fu / kSJ, fsj = prev ? pu % kSJ : fu % kSJ;
       const float s = prev ? sp[G::kSP == 1 ? 0 : pu - (kUnits - 2)]
-                           : sc.s[fsi >> 1][G::kSC == 1 ? 0 : fsj];
+                           : sc.s[G::kSC == 1 ? 0 : fsj];
       st.acc[fsi][fsj][fe] = __builtin_fmaf(st.T[0], s, st.acc[fsi][fsj][fe]);
       st.acc[fsi][fsj][fe + 1] = __builtin_fmaf(st.T[1], s, st.acc[fsi][fsj][fe + 1]);
       pin(st.acc[fsi][fsj][fe], st.acc[fsi][fsj][fe + 1]);
@@ -358,7 +367,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
         int s = -1;
 #pragma unroll
         for (int i = 0; i < kBI; ++i) if (sidx == i) s = r.slot[i];
-        if (s < 0) return;   // unflagged block: nothing to bring (its scale will be zero)
+        if (s < 0) return;   // unflagged block: nothing to bring (its wavefronts skip the item)
         src = p.a_res + (int64_t)s * kBlockBytes + spart;
       } else {
         src = smain + (int64_t)k * kBlockBytes;
@@ -378,9 +387,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
     for (int sj = 0; sj < kSJ; ++sj)
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.acc[si][sj][r] = 0.0f;
-  bool poison[kBI];
-#pragma unroll
-  for (int i = 0; i < kBI; ++i) poison[i] = false;
+  bool poison = false;           // this wavefront's i-block has a flagged block without a slot
 
   if (nkb > 0) {
     // ---- prologue: items 0 and 1 into the two ring slots
@@ -398,7 +405,8 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      st.aq[0][i >> 1][i & 1] = lds_frag(a_ring, 2 * h, i >> 1, i & 1, lane);
+      st.aq[0][i >> 1][i & 1] = lds_frag(a_ring + G::a_block(h, 0) * kBlockBytes, G::a_group(h, 0),
+                                         i >> 1, i & 1, lane);
 #pragma unroll
       for (int j = 0; j < kSJ; ++j) {
         const int cg = kSJ * c + j;
@@ -422,27 +430,28 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
       const int n2k = (n1res || n2res) ? k + 1 : k + 2;
       const bool has2 = n2k < nkb;
 
-      // ---- scales of this item
+      // ---- this wavefront's i-block in this item: its slot, scale, and whether there is work
+      int my_slot = r0.slot[0];
+      float my_sa = res ? r0.rs[0] : r0.sa[0];
+#pragma unroll
+      for (int i = 1; i < kBI; ++i)
+        if (G::a_block(h, 0) == i) {
+          my_slot = r0.slot[i];
+          my_sa = res ? r0.rs[i] : r0.sa[i];
+        }
+      if (!res) poison |= my_slot == -2;
+      // a residual item is work only for the wavefronts whose i-block is flagged at this k
+      const bool active = !res || my_slot >= 0;
       ItemScales<G> sc;
 #pragma unroll
-      for (int i = 0; i < kBI; ++i) {
-        float sa;
-        if (!res) {
-          sa = r0.sa[i];
-          poison[i] |= r0.slot[i] == -2;
-        } else {   // an unflagged block multiplies stale LDS contents by zero: adds +0
-          sa = r0.slot[i] >= 0 ? r0.rs[i] : 0.0f;
-        }
-#pragma unroll
-        for (int q = 0; q < G::kSC; ++q)
-          sc.s[i][q] = sa * ((G::kSC > 1 && sc_is_hi(q)) ? r0.sb[1] : r0.sb[0]);
-      }
+      for (int q = 0; q < G::kSC; ++q)
+        sc.s[q] = my_sa * ((G::kSC > 1 && sc_is_hi(q)) ? r0.sb[1] : r0.sb[0]);
 
       const int8_t* const a_cur = a_ring + (t & 1) * G::kASet;
       const int8_t* const a_nxt = a_ring + ((t + 1) & 1) * G::kASet;
       const int8_t* const b_nxt = b_ring + (n1k & 1) * G::kBSet;
 
-      run_units_range<G, 0, kUnits - 2>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
+      if (active) run_units_range<G, 0, kUnits - 2>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
 
       // All LDS reads of this item are issued (the last two units run from registers).  Wait
       // for them and for the next item's direct-to-LDS loads, then the barrier publishes the
@@ -454,11 +463,26 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
         else stage_item(n2k, 0, r1, t & 1, n2k != n1k);
       }
 
-      run_units_range<G, kUnits - 2, kUnits>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
-
+      if (active) {
+        run_units_range<G, kUnits - 2, kUnits>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
 #pragma unroll
-      for (int i = 0; i < G::kSP; ++i)
-        sp[i] = sc.s[kBI - 1][G::kSC == 1 ? 0 : kSJ - 2 + i];
+        for (int i = 0; i < G::kSP; ++i) sp[i] = sc.s[G::kSC == 1 ? 0 : kSJ - 2 + i];
+      } else {
+        // nothing to multiply in this item: the pipeline state (the pending tile of the last
+        // active item and its scale) stays as it is; only fetch the next item's first operands,
+        // which the last two units would have done
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          st.aq[0][i >> 1][i & 1] = lds_frag(a_nxt + G::a_block(h, 0) * kBlockBytes, G::a_group(h, 0),
+                                             i >> 1, i & 1, lane);
+#pragma unroll
+          for (int j = 0; j < kSJ; ++j) {
+            const int cg = kSJ * c + j;
+            st.bq[j][i >> 1][i & 1] =
+                lds_frag(b_nxt + (cg >> 2) * kBlockBytes, cg & 3, i >> 1, i & 1, lane);
+          }
+        }
+      }
       if (!has1) break;
       // ---- advance to the next item
       ++t;
@@ -486,7 +510,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
 #pragma unroll
   for (int si = 0; si < kSI; ++si) {
     // a flagged block whose residual found no slot cannot be computed: poison its rows
-    const bool bad = poison[si >> 1];
+    const bool bad = poison;
 #pragma unroll
     for (int sj = 0; sj < kSJ; ++sj)
 #pragma unroll
@@ -495,7 +519,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
         const int cl = sj * 32 + 16 * ((e >> 2) & 1) + (lane & 15);
         stg[rl * G::kStagePitch + cl] = bad ? __int_as_float(0x7FC00000) : st.acc[si][sj][e];
       }
-    const int row0 = (ib_first + (si >> 1)) * kBlock + h * 64 + (si & 1) * 32;
+    const int row0 = (ib_first + G::a_block(h, si)) * kBlock + G::a_group(h, si) * 32;
     if (p.out_bf16) {
       uint16_t* const C = reinterpret_cast<uint16_t*>(p.c);
       constexpr int kChunks = G::kStageCols / 8;         // 16-byte chunks per row
