@@ -24,7 +24,7 @@ INT8_PEAK_TOPS = 5000.0     # MI355X dense INT8 MFMA peak (published), TOP/s
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per fq_gemm launch from rocprofv3 FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00), both
 # scaled by what the same counters read for a 1 GiB copy (profiles/gemm_quantize_cfg2_hbm_traffic.md)
-MEASURED_GEMM_TRAFFIC_BYTES = {"cfg2_glu_upgate_4096x4096x11008": 301.5e6 + 90.2e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {"cfg2_glu_upgate_4096x4096x11008": 291.9e6 + 90.2e6}
 
 
 def log(*a):
