@@ -205,8 +205,7 @@ __global__ __launch_bounds__(kCtxThreads) void glu_backward_kernel(GluParams p) 
 // ---- RMS normalization with a fused INT10 context --------------------------------------------
 // One 256-thread workgroup walks a row in chunks of 32 groups (4096 columns): thread t is lane
 // t % 8 of group t / 8 of the chunk, the same team layout as above.
-constexpr int kRowChunkGroups = kCtxThreads / kLanesPerGroup;   // 32
-constexpr int kRowChunkCols = kRowChunkGroups * kCtxGroup;      // 4096
+constexpr int kRowChunkGroups = kCtxThreads / kLanesPerGroup;   // 32 groups = 4096 columns
 constexpr int kRmsMaxChunks = 4;                                // forward keeps rows of up to 4 chunks in registers
 
 __device__ inline LanePos row_pos(int64_t r, int chunk, int ng) {
