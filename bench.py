@@ -63,15 +63,46 @@ def cpu_baseline(wl, budget_s=15.0):
     scale = max(1.0, min(budget_s / max(tc, 1e-3), wl.N / cols))
     cols2 = int(min(wl.N, cols * scale)) // 64 * 64 or cols
     t0 = time.perf_counter()
-    fqo.gemm(fqo.OP_NT, oa, ob, window=(0, rows, 0, cols2))
+    c32, cb16 = fqo.gemm(fqo.OP_NT, oa, ob, window=(0, rows, 0, cols2), want_bf16=True)
     tg = time.perf_counter() - t0
     # quantizing these rows of X is shared by all N columns: charge the window's share
     tq_share = tq * cols2 / wl.N
     ops = 2.0 * rows * cols2 * wl.K
-    return {"value": ops / (tg + tq_share) / 1e12, "unit": "TOPS", "cores": fqo.num_threads(),
+    info = {"value": ops / (tg + tq_share) / 1e12, "unit": "TOPS", "cores": fqo.num_threads(),
             "kind": "oracle",
             "sample": f"oracle fqo_quantize on X[0:{rows}] + fqo_gemm on the {rows}x{cols2} output "
                       f"window (K={wl.K}); {tg:.2f}s gemm + {tq_share:.3f}s quantize share"}
+    return info, (rows, cols2), (c32[:rows, :cols2], cb16[:rows, :cols2])
+
+
+def accuracy(wl, window, oracle_out, y, x, w, qw):
+    """Errors on the output window the CPU oracle has just computed: the GPU result against the
+    oracle (the parity bar: max |diff| / max |ref| <= 1e-3) and, against the exact binary64
+    product of the same bf16 inputs, the GPU result with fallback, plain block INT8 without
+    fallback, and the bf16 GEMM."""
+    import torch
+    import paper_2503_08040_amd as fq
+    from paper_2503_08040_amd import synth
+    rows, cols = window
+    f64 = lambda bits: synth.bf16_bits_to_f32(bits).astype(np.float64)
+    exact = f64(wl.X[:rows]) @ f64(wl.W[:cols]).T
+    ref_max, ref_norm = np.abs(exact).max(), np.linalg.norm(exact)
+
+    def errs(c):
+        d = c.astype(np.float64) - exact
+        return {"max_over_max": float(np.abs(d).max() / ref_max),
+                "frobenius": float(np.linalg.norm(d) / ref_norm)}
+
+    got = y[:rows, :cols].float().cpu().numpy()
+    ref = synth.bf16_bits_to_f32(oracle_out[1]) if y.dtype == torch.bfloat16 else oracle_out[0]
+    qn = fq.fq_quantize(x, fq.FQ_CRIT_NONE, 0.0, capacity=0)
+    plain = fq.fq_gemm(fq.FQ_OP_NT, qn, qw, out_dtype=y.dtype)[:rows, :cols].float().cpu().numpy()
+    bf16 = torch.matmul(x[:rows], w[:cols].t()).float().cpu().numpy()
+    return {"window": f"rows 0:{rows}, columns 0:{cols}",
+            "vs_oracle_max_over_max": float(np.abs(got - ref).max() / np.abs(ref).max()),
+            "vs_oracle_identical": bool(np.array_equal(got, ref)),
+            "vs_fp64": errs(got), "vs_fp64_block_int8_without_fallback": errs(plain),
+            "vs_fp64_bf16_gemm": errs(bf16)}
 
 
 def _time_loop(fn, seconds, iters):
@@ -423,7 +454,9 @@ def main():
                 result["mfma_ceiling"] = json.loads(r.stdout.strip().splitlines()[-1])
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample")
-        result["cpu_baseline"] = cpu_baseline(wl)
+        result["cpu_baseline"], window, oracle_out = cpu_baseline(wl)
+        # the last timed step's output is still in y
+        result["accuracy"] = accuracy(wl, window, oracle_out, y, x, w, qw)
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result), flush=True)
