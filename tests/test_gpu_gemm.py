@@ -237,3 +237,63 @@ def test_full_size_sampled(cfg, monkeypatch):
     assert fq.fq_gemm_tile_plan(wl.M, wl.N)[2] == 0
     gu.announce(f"{cfg}: gemm with a single tile geometry")
     assert torch.equal(fq.fq_gemm(fq.FQ_OP_NT, ga, gb), c32)
+
+
+@pytest.mark.parametrize("variant", ["stochastic", "fallback"])
+def test_full_size_backward_sampled(variant):
+    """Config 2's backward at full size, as the benchmark's backward mode launches it:
+    dX = dY W (NN) and dW = dY^T X (TN) through the transposed copies the quantizer emits.
+    "stochastic": the paper's recipe (Sec. 5.1, 5.3), Q_s(dY) and the Q_s(X) context without
+    fallback; "fallback": config 4's recipe at this size, dY quantized to nearest with about
+    5 % of its blocks flagged, so that both products take residual blocks from the
+    transposed and the plain residual storage.  Quantizer outputs are compared in full, GEMM
+    outputs on sampled windows the oracle computes element by element."""
+    wl = synth.config2()
+    M, K, N = wl.M, wl.K, wl.N
+    rng = np.random.default_rng(21)
+    dy = (rng.standard_t(3.0, size=(M, N)) * 1e-3).astype(F32)
+    dy_bits = synth.to_bf16_bits(dy)
+    gu.announce(f"backward/{variant}: quantize dY {dy.shape}, W, X")
+    if variant == "stochastic":
+        gdy = fq.fq_quantize_sr(gu.to_device_bf16(dy_bits), 7, want_transposed=True)
+        ody = fqo.quantize_sr(dy_bits, 128, 7)
+        gx = fq.fq_quantize_sr(gu.to_device_bf16(wl.X), 5, want_transposed=True)
+        ox = fqo.quantize_sr(wl.X, 128, 5)
+        flagged = np.zeros(0, np.int64)
+    else:
+        amax = np.abs(synth.bf16_bits_to_f32(dy_bits)).reshape(M // 128, 128, N // 128, 128).max(axis=(1, 3))
+        srt = np.sort(amax.ravel())
+        cut = int(0.95 * srt.size)
+        theta = float(0.5 * (srt[cut - 1] + srt[cut]))
+        gdy = fq.fq_quantize(gu.to_device_bf16(dy_bits), fq.FQ_CRIT_ABSMAX_GT, theta, want_transposed=True)
+        ody = fqo.quantize(dy_bits, 128, fqo.CRIT_ABSMAX_GT, theta)
+        gx = fq.fq_quantize(gu.to_device_bf16(wl.X), fq.FQ_CRIT_NONE, 0.0, want_transposed=True)
+        ox = fqo.quantize(wl.X, 128, fqo.CRIT_NONE, 0.0)
+        flagged = ody.fb_list[:ody.fb_count[0]].astype(np.int64)
+        assert 0.03 * amax.size < flagged.size < 0.07 * amax.size
+    gw = fq.fq_quantize(gu.to_device_bf16(wl.W), fq.FQ_CRIT_NONE, 0.0, want_transposed=True)
+    ow = fqo.quantize(wl.W, 128, fqo.CRIT_NONE, 0.0)
+    gu.compare_quantized(gdy, ody, f"backward/{variant} dY")
+    gu.compare_quantized(gx, ox, f"backward/{variant} X")
+    nbc = ody.nbc
+    for op, gb, ob, name in ((fq.FQ_OP_NN, gw, ow, "dX"), (fq.FQ_OP_TN, gx, ox, "dW")):
+        Mo, No = fqo.out_shape(op, ody, ob)
+        assert (Mo, No) == ((M, K) if op == fq.FQ_OP_NN else (N, K))
+        gu.announce(f"backward/{variant}: gemm {name} {Mo}x{No}")
+        c32 = fq.fq_gemm(op, gdy, gb)
+        cb = fq.fq_gemm(op, gdy, gb, out_dtype=torch.bfloat16)
+        torch.cuda.synchronize()
+        # output rows that meet a flagged dY block: its rows for dX, its columns for dW
+        frows = sorted({((int(b) // nbc) if op == fq.FQ_OP_NN else (int(b) % nbc)) * 128
+                        + int(rng.integers(0, 124)) for b in flagged})
+        rng.shuffle(frows)
+        for (i0, i1, j0, j1) in _sampled_windows(rng, Mo, No, frows):
+            ref, refb = fqo.gemm(op, ody, ob, window=(i0, i1, j0, j1), want_bf16=True)
+            got = c32[i0:i1, j0:j1].cpu().numpy()
+            assert gu.rel_err(got, ref[i0:i1, j0:j1]) <= TOL
+            assert np.array_equal(got, ref[i0:i1, j0:j1]), f"{name}: window {(i0, i1, j0, j1)}"
+            gotb = cb[i0:i1, j0:j1].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+            assert np.array_equal(gotb, refb[i0:i1, j0:j1]), f"{name}: bf16 window {(i0, i1, j0, j1)}"
+        assert torch.isfinite(c32).all().item()
+        assert torch.equal(cb, c32.to(torch.bfloat16))
+        del c32, cb
