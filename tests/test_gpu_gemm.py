@@ -180,6 +180,39 @@ def test_capacity_overflow_poisons_output():
     assert torch.isnan(c).any().item()      # never a silently wrong product
 
 
+@pytest.mark.parametrize("shape_a,shape_b,cus", [
+    ((600, 384), (300, 384), 0),      # 256x256 tiles only
+    ((700, 300), (1100, 300), 6),     # 128x384 tiles beside them
+])
+def test_capacity_overflow_poisons_exactly_the_affected_block_rows(shape_a, shape_b, cus, monkeypatch):
+    """Every block is flagged but only some get a residual slot: the rows of an i-block that has
+    a flagged block without a slot are NaN, all other rows are the complete result."""
+    if cus:
+        monkeypatch.setenv("FQ_GEMM_CUS", str(cus))
+    rng = np.random.default_rng(shape_a[0])
+    a_bits = synth.to_bf16_bits(rng.standard_normal(shape_a).astype(F32))
+    b_bits = synth.to_bf16_bits(rng.standard_normal(shape_b).astype(F32) * F32(0.02))
+    nbr, nbc = -(-shape_a[0] // 128), -(-shape_a[1] // 128)
+    ga = fq.fq_quantize(gu.to_device_bf16(a_bits), fq.FQ_CRIT_ALL, 0.0, capacity=(nbr * nbc) // 2)
+    gb = fq.fq_quantize(gu.to_device_bf16(b_bits), fq.FQ_CRIT_NONE, 0.0)
+    with pytest.raises(fq.FqError):
+        fq.fq_qtensor_check(ga)
+    slot = ga.view("fb_slot").cpu().numpy()
+    assert (slot == -2).sum() == nbr * nbc - (nbr * nbc) // 2
+    bad = (slot == -2).any(axis=1)
+    assert bad.any()
+    gu.announce(f"gemm with overflowed residual slots, plan {fq.fq_gemm_tile_plan(shape_a[0], shape_b[0])}")
+    c = fq.fq_gemm(fq.FQ_OP_NT, ga, gb).cpu().numpy()
+    ref = fqo.gemm(fqo.OP_NT, fqo.quantize(a_bits, 128, fqo.CRIT_ALL, 0.0),
+                   fqo.quantize(b_bits, 128, fqo.CRIT_NONE, 0.0))
+    for bi in range(nbr):
+        rows = slice(bi * 128, min((bi + 1) * 128, shape_a[0]))
+        if bad[bi]:
+            assert np.isnan(c[rows]).all(), f"block row {bi} should be poisoned"
+        else:
+            assert np.array_equal(c[rows], ref[rows]), f"block row {bi} should be complete"
+
+
 def _sampled_windows(rng, Mo, No, flagged_rows, n=24, h=4, w=8):
     wins = []
     rows = list(flagged_rows[:n // 2]) + list(rng.integers(0, Mo - h, size=n - len(flagged_rows[:n // 2])))
