@@ -15,8 +15,9 @@
  *   - two-step fallback quantization: quantize G, then quantize the residual
  *     dQ(G) = G - Q(G) with a scale of its own            : Sec. 4.3
  *   - fallback indicator u(i,k) = [max|G_ik| > theta]      : Sec. 4.4
- *     (and the two error-based selectors the section compares it with:
- *     L1 = sum|G - Q(G)| and L1-Rel = L1 / sum|G|, each against theta)
+ *     (and the selectors the section compares it with: the TopK blocks by
+ *     max|G|, and the two error-based ones, L1 = sum|G - Q(G)| and
+ *     L1-Rel = L1 / sum|G|, each against theta)
  *   - block GEMM, INT8 x INT8 -> INT32, dequantized by a^A * a^B and
  *     accumulated in FP32                                  : Sec. 4.2, Eq. (1)
  *   - fallback GEMM: k ascending; main term, then, if u(i,k)=1, the residual
@@ -61,6 +62,7 @@
 #define FQO_CRIT_ALL 2       /* u == 1 everywhere                           */
 #define FQO_CRIT_L1_GT 3     /* u = [sum|G - Q(G)| > theta], Sec. 4.4       */
 #define FQO_CRIT_L1REL_GT 4  /* u = [sum|G - Q(G)| / sum|G| > theta], Sec. 4.4 */
+#define FQO_CRIT_GIVEN 5     /* internal: u is read from `mask` (fqo_quantize_topk) */
 
 #define FQO_OP_NT 0 /* C[M,N] = A[M,K] * B[N,K]^T   (Y  = X  W^T) */
 #define FQO_OP_NN 1 /* C[M,K] = A[M,N] * B[N,K]     (dX = dY W)   */
@@ -90,15 +92,15 @@ static int8_t quantize_one(float x, float a) {
 }
 
 /* Sec. 3.1 (block quantization), Sec. 4.3 (residual step), Sec. 4.4 (u). */
-int fqo_quantize(const uint16_t *x_bf16, int rows, int cols, long ld, int g,
-                 int crit, float theta, int8_t *codes, float *scales,
-                 uint8_t *mask, int8_t *res_codes, float *res_scales,
-                 int32_t *fb_list, int32_t *fb_count) {
+static int quantize_blocks(const uint16_t *x_bf16, int rows, int cols, long ld, int g,
+                           int crit, float theta, int8_t *codes, float *scales,
+                           uint8_t *mask, int8_t *res_codes, float *res_scales,
+                           int32_t *fb_list, int32_t *fb_count) {
   if (!x_bf16 || !codes || !scales || !mask || !res_codes || !res_scales ||
       !fb_list || !fb_count)
     return -1;
   if (rows < 0 || cols < 0 || g < 1 || ld < cols) return -2;
-  if (crit < 0 || crit > 4) return -4;
+  if (crit < 0 || crit > FQO_CRIT_GIVEN) return -4;
   int nbr = (rows + g - 1) / g, nbc = (cols + g - 1) / g;
   int n_fb = 0;
   for (int bi = 0; bi < nbr; ++bi) {
@@ -124,6 +126,7 @@ int fqo_quantize(const uint16_t *x_bf16, int rows, int cols, long ld, int g,
       if (crit == FQO_CRIT_NONE) u = 0;
       else if (crit == FQO_CRIT_ALL) u = 1;
       else if (crit == FQO_CRIT_ABSMAX_GT) u = (amax > theta) ? 1 : 0;
+      else if (crit == FQO_CRIT_GIVEN) u = mask[bi * nbc + bk] ? 1 : 0;
       else {
         /* block quantization error L1 = sum |G - Q(G)| and sum |G|, summed in binary64 over
          * the binary32 residuals (the same residual the second step quantizes) */
@@ -168,6 +171,54 @@ int fqo_quantize(const uint16_t *x_bf16, int rows, int cols, long ld, int g,
   }
   *fb_count = n_fb;
   return 0;
+}
+
+int fqo_quantize(const uint16_t *x_bf16, int rows, int cols, long ld, int g,
+                 int crit, float theta, int8_t *codes, float *scales,
+                 uint8_t *mask, int8_t *res_codes, float *res_scales,
+                 int32_t *fb_list, int32_t *fb_count) {
+  if (crit < 0 || crit > FQO_CRIT_L1REL_GT) return -4;
+  return quantize_blocks(x_bf16, rows, cols, ld, g, crit, theta, codes, scales, mask,
+                         res_codes, res_scales, fb_list, fb_count);
+}
+
+/*
+ * TopK AbsMax selection (Sec. 4.4): the k blocks with the largest max|G| fall back
+ * (all of them if k is at least the number of blocks, none if k <= 0).  The paper does
+ * not say what happens among equal values: here the block with the lower index
+ * (bi*nbc + bk) goes first, which makes the selection unique.  Written as k rounds of
+ * "take the largest block not taken yet"; everything else is fqo_quantize.
+ */
+int fqo_quantize_topk(const uint16_t *x_bf16, int rows, int cols, long ld, int g, int k,
+                      int8_t *codes, float *scales, uint8_t *mask, int8_t *res_codes,
+                      float *res_scales, int32_t *fb_list, int32_t *fb_count) {
+  if (!x_bf16 || !mask) return -1;
+  if (rows < 0 || cols < 0 || g < 1 || ld < cols) return -2;
+  int nbr = (rows + g - 1) / g, nbc = (cols + g - 1) / g, nb = nbr * nbc;
+  float *amax = (float *)malloc(sizeof(float) * (size_t)(nb > 0 ? nb : 1));
+  if (!amax) return -7;
+  for (int bi = 0; bi < nbr; ++bi)
+    for (int bk = 0; bk < nbc; ++bk) {
+      int r1 = (bi + 1) * g < rows ? (bi + 1) * g : rows;
+      int c1 = (bk + 1) * g < cols ? (bk + 1) * g : cols;
+      float m = 0.0f;
+      for (int r = bi * g; r < r1; ++r)
+        for (int c = bk * g; c < c1; ++c) {
+          float v = fabsf(bf16_to_f32(x_bf16[(size_t)r * ld + c]));
+          if (v > m) m = v;
+        }
+      amax[bi * nbc + bk] = m;
+    }
+  for (int b = 0; b < nb; ++b) mask[b] = 0;
+  for (int n = 0; n < k && n < nb; ++n) {
+    int best = -1;
+    for (int b = 0; b < nb; ++b)
+      if (!mask[b] && (best < 0 || amax[b] > amax[best])) best = b;
+    mask[best] = 1;
+  }
+  free(amax);
+  return quantize_blocks(x_bf16, rows, cols, ld, g, FQO_CRIT_GIVEN, 0.0f, codes, scales, mask,
+                         res_codes, res_scales, fb_list, fb_count);
 }
 
 /*

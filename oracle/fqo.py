@@ -32,6 +32,9 @@ def lib():
         _lib.fqo_quantize.restype = C.c_int
         _lib.fqo_quantize.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_long, C.c_int, C.c_int,
                                       C.c_float] + [C.c_void_p] * 7
+        _lib.fqo_quantize_topk.restype = C.c_int
+        _lib.fqo_quantize_topk.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_long, C.c_int,
+                                           C.c_int] + [C.c_void_p] * 7
         _lib.fqo_gemm.restype = C.c_int
         _lib.fqo_gemm.argtypes = [C.c_int, C.POINTER(_Operand), C.POINTER(_Operand), C.c_int,
                                   C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -114,6 +117,22 @@ def quantize(x_bf16: np.ndarray, g: int, crit: int, theta: float) -> QTensor:
                             q.fb_list.ctypes.data, q.fb_count.ctypes.data)
     if rc != 0:
         raise RuntimeError(f"fqo_quantize failed: {rc}")
+    return q
+
+
+def quantize_topk(x_bf16: np.ndarray, g: int, k: int) -> QTensor:
+    """TopK AbsMax selection (Sec. 4.4): the k blocks with the largest abs-max fall back."""
+    assert x_bf16.dtype == np.uint16 and x_bf16.ndim == 2
+    assert x_bf16.strides[1] == 2 and x_bf16.strides[0] % 2 == 0
+    rows, cols = x_bf16.shape
+    ld = x_bf16.strides[0] // 2 if rows > 1 else max(cols, 1)
+    q = QTensor(rows, cols, g)
+    rc = lib().fqo_quantize_topk(x_bf16.ctypes.data, rows, cols, ld, g, int(k),
+                                 q.codes.ctypes.data, q.scales.ctypes.data, q.mask.ctypes.data,
+                                 q.res_codes.ctypes.data, q.res_scales.ctypes.data,
+                                 q.fb_list.ctypes.data, q.fb_count.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"fqo_quantize_topk failed: {rc}")
     return q
 
 
