@@ -122,6 +122,44 @@ def _time_loop(fn, seconds, iters):
     return e0.elapsed_time(e1) / iters
 
 
+def criteria(args):
+    """Quantizer time under each fallback selector of Sec. 4.4 on the workload's X, every one
+    set to flag the same number of blocks (the workload's planted outlier blocks)."""
+    import torch
+    import paper_2503_08040_amd as fq
+    wl = make_workload(args.workload)
+    x = torch.from_numpy(wl.X.view(np.int16)).cuda().view(torch.bfloat16)
+    M, K = wl.M, wl.K
+    out = fq.QTensor(M, K)
+    k = len(wl.flagged_blocks)
+    nb = out.nbr * out.nbc
+    rows = []
+
+    def add(name, fn, bytes_per_elt):
+        ms = _time_loop(fn, 0.5, 100)
+        n = fq.fq_qtensor_check(out)
+        nbytes = bytes_per_elt(n / nb) * M * K
+        rows.append({"selector": name, "flagged": n, "ms": round(ms, 5),
+                     "algorithmic_gbs": round(nbytes / ms / 1e6, 1),
+                     "frac_of_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)})
+
+    add("none", lambda: fq.fq_quantize(x, fq.FQ_CRIT_NONE, 0.0, out=out), lambda f: 3.0)
+    add("absmax > theta", lambda: fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, wl.theta, out=out),
+        lambda f: 3.0 + f)
+    add(f"top-{k} absmax", lambda: fq.fq_quantize_topk(x, k, out=out), lambda f: 5.0 + f)
+    # L1 threshold between the k-th and (k+1)-th largest block error, found by bisection on the count
+    lo, hi = 0.0, 1e9
+    for _ in range(60):
+        mid = 0.5 * (lo + hi)
+        fq.fq_quantize(x, fq.FQ_CRIT_L1_GT, mid, out=out)
+        if fq.fq_qtensor_check(out) > k:
+            lo = mid
+        else:
+            hi = mid
+    add("L1 > theta", lambda: fq.fq_quantize(x, fq.FQ_CRIT_L1_GT, hi, out=out), lambda f: 3.0 + f)
+    return {"workload": wl.name + "_selectors", "rows": M, "cols": K, "blocks": nb, "selectors": rows}
+
+
 def sweep(args):
     """BASELINE config 5: M = K = N = 8192, fallback fraction and placement swept."""
     import torch
@@ -296,6 +334,9 @@ def main():
     ap.add_argument("--context", action="store_true",
                     help="time the INT10 1x128 context compression / decompression of the "
                          "workload's X instead (GB/s against the HBM roofline)")
+    ap.add_argument("--criteria", action="store_true",
+                    help="time the quantizer under each fallback selector (threshold, top-k, L1) "
+                         "on the workload's X instead")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 1 GiB (5 times) and exit: gives the "
                          "profiler's FETCH_SIZE / WRITE_SIZE counters a kernel of known traffic")
@@ -326,6 +367,9 @@ def main():
         return
     if args.context:
         print(json.dumps(context(args)), flush=True)
+        return
+    if args.criteria:
+        print(json.dumps(criteria(args)), flush=True)
         return
     log(f"[bench] generating {args.workload}")
     wl = make_workload(args.workload)

@@ -79,10 +79,13 @@ typedef enum {
  *   are binary64 accumulations of the binary32 terms in unspecified order and the comparison
  *   is binary64, so a block whose metric is within about 2^-40 (relative) of theta may be
  *   decided either way.  These two cost one extra pass over the block in registers.
- * (Selecting the top-k blocks of a tensor needs a tensor-wide reduction; the paper replaces
- * it by the delayed threshold of App. D, see fq_threshold_update.) */
+ *   FQ_CRIT_TOPK       the k blocks with the largest max|G| (Sec. 4.4): not accepted by
+ *                      fq_quantize, which has no k; it is what fq_quantize_topk records in
+ *                      the tensor.  It needs a tensor-wide selection, which is why the paper
+ *                      replaces it by the delayed threshold of App. D (fq_threshold_update). */
 typedef enum {
-  FQ_CRIT_NONE = 0, FQ_CRIT_ABSMAX_GT = 1, FQ_CRIT_ALL = 2, FQ_CRIT_L1_GT = 3, FQ_CRIT_L1REL_GT = 4
+  FQ_CRIT_NONE = 0, FQ_CRIT_ABSMAX_GT = 1, FQ_CRIT_ALL = 2, FQ_CRIT_L1_GT = 3, FQ_CRIT_L1REL_GT = 4,
+  FQ_CRIT_TOPK = 5
 } fq_criterion;
 
 /* Which product of the linear layer (Sec. 3.2).  A is the operand that may
@@ -161,6 +164,21 @@ fq_status fq_qtensor_bind(void *base, int32_t rows, int32_t cols, int32_t block,
 fq_status fq_quantize(const void *x_bf16, int32_t rows, int32_t cols, int64_t ld,
                       int32_t block, fq_criterion crit, float theta, fq_qtensor *out,
                       void *hip_stream);
+
+/*
+ * TopK AbsMax selection (Sec. 4.4): as fq_quantize, but u = 1 for the k blocks with the
+ * largest max|G| (every block if k >= nbr*nbc, none if k <= 0).  Among blocks with equal
+ * max|G| the lower block id bi*nbc + bk is taken first (the paper leaves this open), so the
+ * result is unique.  Three launches on `hip_stream`: max|G| of every block (kept in
+ * out->scales until the last launch overwrites it with the scales), the selection (one
+ * workgroup: a radix select over the nbr*nbc values), and the fused quantizer with that
+ * selection as its decision; the input is read twice, (5 + f) bytes per element instead of
+ * (3 + f).  out->criterion becomes FQ_CRIT_TOPK.  The number of flagged blocks is known
+ * beforehand: FQ_ERR_CAPACITY if out->capacity < min(max(k, 0), nbr*nbc).  Other arguments,
+ * outputs and errors as fq_quantize.
+ */
+fq_status fq_quantize_topk(const void *x_bf16, int32_t rows, int32_t cols, int64_t ld,
+                           int32_t block, int32_t k, fq_qtensor *out, void *hip_stream);
 
 /*
  * Block INT8 quantization with stochastic rounding (Sec. 3.1: x is rounded up with

@@ -15,14 +15,15 @@ FQ_CTX_GROUP_BYTES = 160
 
 FQ_OK, FQ_ERR_NULL, FQ_ERR_SHAPE, FQ_ERR_BLOCK, FQ_ERR_ENUM, FQ_ERR_CAPACITY, FQ_ERR_HIP = \
     0, -1, -2, -3, -4, -5, -6
-FQ_CRIT_NONE, FQ_CRIT_ABSMAX_GT, FQ_CRIT_ALL, FQ_CRIT_L1_GT, FQ_CRIT_L1REL_GT = 0, 1, 2, 3, 4
+FQ_CRIT_NONE, FQ_CRIT_ABSMAX_GT, FQ_CRIT_ALL, FQ_CRIT_L1_GT, FQ_CRIT_L1REL_GT, FQ_CRIT_TOPK = \
+    0, 1, 2, 3, 4, 5
 FQ_OP_NT, FQ_OP_NN, FQ_OP_TN = 0, 1, 2
 FQ_OUT_F32, FQ_OUT_BF16 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfq.so")
 
-EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr",
+EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr", "fq_quantize_topk",
            "fq_threshold_update", "fq_gemm",
            "fq_gemm_debug_partials", "fq_codes_to_rowmajor", "fq_qtensor_check",
            "fq_status_string", "fq_ctx_packed_bytes", "fq_ctx_scales_bytes", "fq_ctx_quantize",
@@ -69,6 +70,9 @@ def lib():
         L.fq_quantize_sr.restype = C.c_int
         L.fq_quantize_sr.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int32,
                                      C.c_uint64, C.POINTER(fq_qtensor), C.c_void_p]
+        L.fq_quantize_topk.restype = C.c_int
+        L.fq_quantize_topk.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int64, C.c_int32,
+                                       C.c_int32, C.POINTER(fq_qtensor), C.c_void_p]
         L.fq_threshold_update.restype = C.c_float
         L.fq_threshold_update.argtypes = [C.c_float, C.c_int32, C.c_int32, C.c_float, C.c_float,
                                           C.c_float]
@@ -210,6 +214,21 @@ def fq_quantize_sr(x, seed, out: QTensor = None, want_transposed=False, stream=N
     _check(lib().fq_quantize_sr(C.c_void_p(x.data_ptr()), rows, cols, ld, FQ_BLOCK,
                                 C.c_uint64(seed), C.byref(out.c), _stream_ptr(stream)),
            "fq_quantize_sr")
+    return out
+
+
+def fq_quantize_topk(x, k, out: QTensor = None, capacity=None, want_transposed=False,
+                     stream=None) -> QTensor:
+    """As fq_quantize, with the k blocks of largest abs-max falling back (Sec. 4.4)."""
+    import torch
+    assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.is_cuda
+    assert x.stride(1) == 1 or x.shape[1] <= 1
+    rows, cols = x.shape
+    ld = x.stride(0) if rows > 1 else max(cols, 1)
+    if out is None:
+        out = QTensor(rows, cols, capacity, want_transposed, x.device)
+    _check(lib().fq_quantize_topk(C.c_void_p(x.data_ptr()), rows, cols, ld, FQ_BLOCK, int(k),
+                                  C.byref(out.c), _stream_ptr(stream)), "fq_quantize_topk")
     return out
 
 

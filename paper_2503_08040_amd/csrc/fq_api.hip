@@ -57,7 +57,7 @@ fq_status prepare_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, fq::G
   if (s != FQ_OK) return s;
   if (op != FQ_OP_NT && op != FQ_OP_NN && op != FQ_OP_TN) return FQ_ERR_ENUM;
   if (B->criterion != FQ_CRIT_NONE) return FQ_ERR_ENUM;
-  if (A->criterion < FQ_CRIT_NONE || A->criterion > FQ_CRIT_L1REL_GT) return FQ_ERR_ENUM;
+  if (A->criterion < FQ_CRIT_NONE || A->criterion > FQ_CRIT_TOPK) return FQ_ERR_ENUM;
   const bool a_fb = A->criterion != FQ_CRIT_NONE;
   if (a_fb && A->capacity == 0) return FQ_ERR_CAPACITY;
   const int a_nbr = (int)ceil_div(A->rows, FQ_BLOCK), a_nbc = (int)ceil_div(A->cols, FQ_BLOCK);
@@ -134,24 +134,30 @@ fq_status fq_qtensor_bind(void* base, int32_t rows, int32_t cols, int32_t block,
 namespace {
 fq_status quantize_impl(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld, int32_t block,
                         fq_criterion crit, float theta, int stochastic, uint64_t seed,
-                        fq_qtensor* out, void* hip_stream) {
+                        int32_t topk, fq_qtensor* out, void* hip_stream) {
   if (!out) return FQ_ERR_NULL;
   if (block != FQ_BLOCK) return FQ_ERR_BLOCK;
   if (rows < 0 || cols < 0 || ld < cols) return FQ_ERR_SHAPE;
-  if (crit < FQ_CRIT_NONE || crit > FQ_CRIT_L1REL_GT) return FQ_ERR_ENUM;
+  if (crit < FQ_CRIT_NONE || crit > FQ_CRIT_TOPK) return FQ_ERR_ENUM;
   fq_status s = check_qtensor(out);
   if (s != FQ_OK) return s;
   if (out->rows != rows || out->cols != cols) return FQ_ERR_SHAPE;
   const bool empty = rows == 0 || cols == 0;
   if (!empty && !x_bf16) return FQ_ERR_NULL;
-  if (crit != FQ_CRIT_NONE && out->capacity == 0 && !empty) return FQ_ERR_CAPACITY;
+  if (crit == FQ_CRIT_TOPK) {
+    // the number of flagged blocks is known here, so a tensor that cannot hold them is refused
+    const int64_t nb = ceil_div(rows, FQ_BLOCK) * ceil_div(cols, FQ_BLOCK);
+    if (std::min<int64_t>(std::max<int64_t>(topk, 0), nb) > out->capacity) return FQ_ERR_CAPACITY;
+  } else if (crit != FQ_CRIT_NONE && out->capacity == 0 && !empty) {
+    return FQ_ERR_CAPACITY;
+  }
 
   fq::QuantParams p{};
   p.x = static_cast<const uint16_t*>(x_bf16);
   p.rows = rows; p.cols = cols; p.ld = ld;
   p.nbr = (int)ceil_div(rows, FQ_BLOCK); p.nbc = (int)ceil_div(cols, FQ_BLOCK);
   p.vec_ok = (((uintptr_t)x_bf16 & 15) == 0 && (ld % 8) == 0) ? 1 : 0;
-  p.crit = (int)crit; p.theta = theta; p.capacity = out->capacity;
+  p.crit = (int)crit; p.theta = theta; p.topk = topk; p.capacity = out->capacity;
   p.stochastic = stochastic; p.seed = seed;
   p.codes = out->codes; p.codes_t = out->codes_t;
   p.scales = out->scales; p.mask = out->mask;
@@ -174,12 +180,18 @@ fq_status quantize_impl(const void* x_bf16, int32_t rows, int32_t cols, int64_t 
 
 fq_status fq_quantize(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld, int32_t block,
                       fq_criterion crit, float theta, fq_qtensor* out, void* hip_stream) {
-  return quantize_impl(x_bf16, rows, cols, ld, block, crit, theta, 0, 0, out, hip_stream);
+  if (crit == FQ_CRIT_TOPK) return FQ_ERR_ENUM;   // that selection takes k: fq_quantize_topk
+  return quantize_impl(x_bf16, rows, cols, ld, block, crit, theta, 0, 0, 0, out, hip_stream);
+}
+
+fq_status fq_quantize_topk(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld, int32_t block,
+                           int32_t k, fq_qtensor* out, void* hip_stream) {
+  return quantize_impl(x_bf16, rows, cols, ld, block, FQ_CRIT_TOPK, 0.0f, 0, 0, k, out, hip_stream);
 }
 
 fq_status fq_quantize_sr(const void* x_bf16, int32_t rows, int32_t cols, int64_t ld, int32_t block,
                          uint64_t seed, fq_qtensor* out, void* hip_stream) {
-  return quantize_impl(x_bf16, rows, cols, ld, block, FQ_CRIT_NONE, 0.0f, 1, seed, out, hip_stream);
+  return quantize_impl(x_bf16, rows, cols, ld, block, FQ_CRIT_NONE, 0.0f, 1, seed, 0, out, hip_stream);
 }
 
 float fq_threshold_update(float theta, int32_t n_fallback, int32_t n_blocks, float r_min,

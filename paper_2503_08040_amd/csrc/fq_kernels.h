@@ -15,6 +15,7 @@ struct QuantParams {
   int stochastic;      // 1: stochastic rounding with `seed` (crit must be 0)
   uint64_t seed;
   float theta;
+  int topk;            // crit 5: number of blocks that fall back (largest abs-max first)
   int capacity;
   int8_t* codes;
   int8_t* codes_t;     // nullptr: no transposed copies

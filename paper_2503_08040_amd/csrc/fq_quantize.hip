@@ -132,12 +132,57 @@ __device__ inline void store_transposed(const v4i (&q)[4], int rp, int cc, int8_
   for (int i = 0; i < 4; ++i) out[i * kThreads + threadIdx.x] = src[i * kThreads + threadIdx.x];
 }
 
+// Thread (rp, cc) of the workgroup that owns block (bi, bk) loads its 4 x 16 bf16 values
+// (rows rp + 32 pz, columns 16 cc ...), zero outside the matrix.
+__device__ __forceinline__ void load_block(const QuantParams& p, int bi, int bk, int rp, int cc,
+                                  v4i (&raw)[4][2]) {
+  const int row0 = bi * kBlock, col0 = bk * kBlock + cc * 16;
+  const bool inner = (row0 + kBlock <= p.rows) && (bk * kBlock + kBlock <= p.cols) && p.vec_ok;
+  if (inner) {
+#pragma unroll
+    for (int pz = 0; pz < 4; ++pz) {
+      const uint16_t* src = p.x + (int64_t)(row0 + pz * 32 + rp) * p.ld + col0;
+      raw[pz][0] = *reinterpret_cast<const v4i*>(src);
+      raw[pz][1] = *reinterpret_cast<const v4i*>(src + 8);
+    }
+  } else {
+#pragma unroll
+    for (int pz = 0; pz < 4; ++pz) {
+      const int r = row0 + pz * 32 + rp;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const int c = col0 + 2 * d + hh;
+          if (r < p.rows && c < p.cols) w |= (uint32_t)p.x[(int64_t)r * p.ld + c] << (16 * hh);
+        }
+        raw[pz][d >> 2][d & 3] = (int)w;
+      }
+    }
+  }
+}
+
+// max |G| of this thread's values
+__device__ __forceinline__ float thread_absmax(const v4i (&raw)[4][2]) {
+  float m = 0.0f;
+#pragma unroll
+  for (int pz = 0; pz < 4; ++pz)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) m = fmaxf(m, fabsf(x_at(raw, pz, e)));
+  return m;
+}
+
 }  // namespace
 
 // kErr: the fallback decision uses a block quantization-error metric (criteria 3, 4), which
 // needs the residual of every block, not only of the flagged ones.
+// (The error-metric variants need the block's residuals and two binary64 sums on top of the
+// packed state: under the 128-register limit of four workgroups per compute unit they spill,
+// and run a quarter faster with two workgroups and no spills.)
 template <bool kWantT, bool kStochastic, bool kErr>
-__global__ __launch_bounds__(kThreads, 4) void quantize_kernel(QuantParams p) {
+__global__ __launch_bounds__(kThreads, kErr ? 2 : 4)
+void quantize_kernel(QuantParams p) {
   __shared__ float red[4];
   __shared__ double redd[kErr ? 8 : 1];
   __shared__ int slot_sh;
@@ -192,7 +237,8 @@ __global__ __launch_bounds__(kThreads, 4) void quantize_kernel(QuantParams p) {
   bool u = false;
   int slot_early = -1;
   if (!kErr) {
-    u = p.crit == 2 || (p.crit == 1 && amax > p.theta);
+    // criterion 5: the decision was taken by topk_select_kernel and is read from the mask
+    u = p.crit == 2 || (p.crit == 1 && amax > p.theta) || (p.crit == 5 && p.mask[blk] != 0);
     if (u && t == 0) slot_early = atomicAdd(p.fb_count, 1);
   }
 
@@ -311,6 +357,100 @@ __global__ __launch_bounds__(kThreads, 4) void quantize_kernel(QuantParams p) {
   if (t == 0) p.res_scales[slot] = ra;
 }
 
+// ---- TopK AbsMax selection (Sec. 4.4), in three launches: the abs-max of every block, the
+// tensor-wide choice of the k largest, then quantize_kernel with that choice as its decision.
+
+// max |G| of each block into amax[nbr * nbc] (the tensor's scale array serves as that buffer
+// until quantize_kernel overwrites it with the scales).
+__global__ __launch_bounds__(kThreads, 4) void block_absmax_kernel(QuantParams p) {
+  __shared__ float red[4];
+  const int blk = blockIdx.x;
+  const int bi = blk / p.nbc, bk = blk - bi * p.nbc;
+  v4i raw[4][2];
+  load_block(p, bi, bk, threadIdx.x >> 3, threadIdx.x & 7, raw);
+  const float amax = block_max(thread_absmax(raw), red);
+  if (threadIdx.x == 0) p.scales[blk] = amax;
+}
+
+constexpr int kSelectThreads = 1024;
+
+// mask[b] = 1 for the k blocks with the largest amax (0 < k < nb), equal values in ascending
+// block order.  One workgroup: a radix select over the bit patterns (non-negative binary32
+// values order like unsigned integers) finds the k-th largest value T in four passes of 8
+// bits; then everything above T is flagged, and of the blocks equal to T the first ones in
+// index order, as many as are still missing.
+__global__ __launch_bounds__(kSelectThreads) void topk_select_kernel(const float* amax, int nb,
+                                                                    int k, uint8_t* mask) {
+  __shared__ int hist[256], suffix[256];
+  __shared__ int sel_bin, sel_want;
+  __shared__ int wave_total[kSelectThreads / 64];
+  __shared__ int running;
+  const int t = threadIdx.x;
+  uint32_t prefix = 0, known = 0;
+  int want = k;            // the value looked for is the want-th largest among those matching prefix
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    if (t < 256) hist[t] = 0;
+    __syncthreads();
+    for (int i = t; i < nb; i += kSelectThreads) {
+      const uint32_t b = __float_as_uint(amax[i]);
+      if ((b & known) == prefix) atomicAdd(&hist[(b >> shift) & 255], 1);
+    }
+    __syncthreads();
+    // the bin holding the want-th largest candidate: the one whose count of candidates in
+    // bins >= it reaches `want` while the count in bins above it does not.  suffix[b] = sum of
+    // hist[b..255] by a 256-wide parallel scan.
+    if (t < 256) suffix[t] = hist[t];
+    __syncthreads();
+    for (int step = 1; step < 256; step <<= 1) {
+      int add = 0;
+      if (t < 256 && t + step < 256) add = suffix[t + step];
+      __syncthreads();
+      if (t < 256) suffix[t] += add;
+      __syncthreads();
+    }
+    if (t < 256) {
+      const int above = t < 255 ? suffix[t + 1] : 0;
+      if (suffix[t] >= want && above < want) {
+        sel_bin = t;
+        sel_want = want - above;
+      }
+    }
+    __syncthreads();
+    prefix |= (uint32_t)sel_bin << shift;
+    known |= 255u << shift;
+    want = sel_want;
+    __syncthreads();       // sel_* and hist are rewritten in the next pass
+  }
+  const uint32_t T = prefix;     // `want` of the blocks equal to T are taken
+  if (t == 0) running = 0;
+  __syncthreads();
+  const int lane = t & 63, w = t >> 6;
+  for (int base = 0; base < nb; base += kSelectThreads) {
+    const int i = base + t;
+    const uint32_t b = i < nb ? __float_as_uint(amax[i]) : 0u;
+    const bool eq = i < nb && b == T;
+    const unsigned long long ballot = __ballot(eq);
+    const int before_in_wave = __popcll(ballot & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_total[w] = __popcll(ballot);
+    __syncthreads();
+    int before = running, chunk = 0;
+    for (int j = 0; j < kSelectThreads / 64; ++j) {
+      if (j < w) before += wave_total[j];
+      chunk += wave_total[j];
+    }
+    if (i < nb) mask[i] = (b > T || (eq && before + before_in_wave < want)) ? 1 : 0;
+    __syncthreads();
+    if (t == 0) running += chunk;
+    __syncthreads();
+  }
+}
+
+// mask[b] = v for every block (k <= 0 or k >= number of blocks).
+__global__ void fill_mask_kernel(uint8_t* mask, int nb, int v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < nb) mask[i] = (uint8_t)v;
+}
+
 // Clears both slot counters: first use of a tensor, or an empty input.
 __global__ void clear_counters_kernel(int32_t* live, int32_t* next) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
@@ -332,9 +472,19 @@ hipError_t launch_quantize(const QuantParams& p, hipStream_t st) {
   if (p.clear_both)
     hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, st, p.fb_count, p.fb_count_next);
   const int nb = p.nbr * p.nbc;
+  if (nb > 0 && p.crit == 5) {
+    if (p.topk <= 0 || p.topk >= nb) {
+      hipLaunchKernelGGL(fill_mask_kernel, dim3((nb + 255) / 256), dim3(256), 0, st, p.mask, nb,
+                         p.topk > 0 ? 1 : 0);
+    } else {
+      hipLaunchKernelGGL(block_absmax_kernel, dim3(nb), dim3(kThreads), 0, st, p);
+      hipLaunchKernelGGL(topk_select_kernel, dim3(1), dim3(kSelectThreads), 0, st, p.scales, nb,
+                         p.topk, p.mask);
+    }
+  }
   if (nb > 0) {
     const dim3 grid(nb), block(kThreads);
-    const bool err = p.crit >= 3;
+    const bool err = p.crit == 3 || p.crit == 4;
     if (p.stochastic) {
       if (p.codes_t) hipLaunchKernelGGL((quantize_kernel<true, true, false>), grid, block, 0, st, p);
       else hipLaunchKernelGGL((quantize_kernel<false, true, false>), grid, block, 0, st, p);
