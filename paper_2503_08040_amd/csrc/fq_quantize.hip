@@ -11,6 +11,8 @@
 // holds 4 rows x 16 consecutive columns in registers: column chunk t%8, rows
 // t/8 + 32*p.  A 16-column chunk is exactly one lane's 16 bytes of a tile-order
 // fragment, so codes leave as 16-byte stores.
+#include <type_traits>
+
 #include "fq_device.h"
 #include "fq_kernels.h"
 
@@ -65,8 +67,10 @@ __device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint
   uint32_t c2 = 0, c3 = 0;
 #pragma unroll
   for (int round = 0; round < 10; ++round) {
-    const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
-    const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+    // one 32 x 32 -> 64-bit multiplication per product (a single instruction on this target)
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t h0 = (uint32_t)(p0 >> 32), l0 = (uint32_t)p0;
+    const uint32_t h1 = (uint32_t)(p1 >> 32), l1 = (uint32_t)p1;
     c0 = h1 ^ c1 ^ k0;
     c1 = l1;
     c2 = h0 ^ c3 ^ k1;
@@ -254,31 +258,35 @@ void quantize_kernel(QuantParams p) {
       }
     }
   } else {
-    // element (r, c) uses word (r*cols + c) & 3 of the Philox block with counter (r*cols + c) >> 2
+    // element (r, c) uses word (r*cols + c) & 3 of the Philox block with counter (r*cols + c) >> 2.
+    // A thread's 16 consecutive elements of a row start at word `off` of a block and span 4
+    // blocks (off = 0) or 5; off is the same for its four rows (they are 32*cols elements apart).
     const uint32_t k0 = (uint32_t)p.seed, k1 = (uint32_t)(p.seed >> 32);
+    auto rows_at = [&](auto off_c) {
+      constexpr int off = decltype(off_c)::value;
+      constexpr int kBlocks = off ? 5 : 4;
 #pragma unroll
-    for (int pz = 0; pz < 4; ++pz) {
-      const uint64_t e0 = (uint64_t)(row0 + pz * 32 + rp) * (uint64_t)p.cols + (uint64_t)col0;
-      if ((e0 & 3) == 0) {   // 16 columns = 4 whole Philox blocks
+      for (int pz = 0; pz < 4; ++pz) {
+        const uint64_t e0 = (uint64_t)(row0 + pz * 32 + rp) * (uint64_t)p.cols + (uint64_t)col0;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
+        for (int b = 0; b < kBlocks; ++b) {
           uint32_t w[4];
           const uint64_t ctr = (e0 >> 2) + b;
           philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), k0, k1, w);
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            put_code(q[pz], 4 * b + i,
-                     (a == 0.0f) ? 0 : quantize_one_sr(x_at(raw, pz, 4 * b + i), a, w[i]));
-        }
-      } else {               // row pitch not a multiple of 4: one block per element
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          uint32_t w[4];
-          const uint64_t el = e0 + e, ctr = el >> 2;
-          philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), k0, k1, w);
-          put_code(q[pz], e, (a == 0.0f) ? 0 : quantize_one_sr(x_at(raw, pz, e), a, w[el & 3]));
+          for (int i = 0; i < 4; ++i) {
+            const int e = 4 * b + i - off;      // compile-time after unrolling
+            if (e >= 0 && e < 16)
+              put_code(q[pz], e, (a == 0.0f) ? 0 : quantize_one_sr(x_at(raw, pz, e), a, w[i]));
+          }
         }
       }
+    };
+    switch ((int)(((uint64_t)(row0 + rp) * (uint64_t)p.cols + (uint64_t)col0) & 3)) {
+      case 0: rows_at(std::integral_constant<int, 0>{}); break;
+      case 1: rows_at(std::integral_constant<int, 1>{}); break;
+      case 2: rows_at(std::integral_constant<int, 2>{}); break;
+      default: rows_at(std::integral_constant<int, 3>{}); break;
     }
   }
 
