@@ -39,7 +39,7 @@ def test_random_case(seed, monkeypatch):
     sa = {0: (m, k), 1: (m, k), 2: (k, m)}[op]          # NT: A[M,K]  NN: A[M,K]  TN: A[K,M]
     sb = {0: (n, k), 1: (k, n), 2: (k, n)}[op]          # NT: B[N,K]  NN: B[K,N]  TN: B[K,N]
     a_bits, b_bits = _matrix(rng, sa, True), _matrix(rng, sb, False)
-    mode = ["absmax", "all", "none", "l1", "sr"][int(rng.integers(0, 5))]
+    mode = ["absmax", "all", "none", "l1", "sr", "topk"][int(rng.integers(0, 6))]
     monkeypatch.setenv("FQ_GEMM_CUS", str(int(rng.choice([1, 2, 3, 5, 7, 256]))))
     label = f"seed={seed} op={op} A{sa} B{sb} mode={mode}"
     gu.announce(label)
@@ -48,6 +48,11 @@ def test_random_case(seed, monkeypatch):
         s = int(rng.integers(0, 2 ** 62))
         ga = fq.fq_quantize_sr(ad, s, want_transposed=True)
         oa = fqo.quantize_sr(a_bits, 128, s)
+    elif mode == "topk":
+        nb = (-(-sa[0] // 128)) * (-(-sa[1] // 128))
+        kk = int(rng.integers(0, nb + 2))
+        ga = fq.fq_quantize_topk(ad, kk, want_transposed=True)
+        oa = fqo.quantize_topk(a_bits, 128, kk)
     else:
         amax = np.abs(synth.bf16_bits_to_f32(a_bits)).max()
         crit, ocrit, theta = {
