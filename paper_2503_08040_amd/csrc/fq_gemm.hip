@@ -36,6 +36,7 @@
 // main term then residual term) in both geometries, so results match a
 // sequential evaluation bit for bit and do not depend on the tile plan.
 #include <algorithm>
+#include <atomic>
 #include <cstdlib>
 
 #include "fq_device.h"
@@ -46,6 +47,7 @@ namespace fq {
 namespace {
 
 constexpr int kThreads = 512;
+constexpr int kMaxDevices = 64;   // per-device host-side caches
 constexpr int kXcds = 8;      // accelerator complex dies, each with a private L2
 constexpr int kGroupN = 4;    // tile columns per rasterization group
 constexpr int kRingBytes = 2 * kBlockBytes;     // one A pair or one B pair
@@ -676,16 +678,18 @@ int planning_cus() {
     const int v = std::atoi(e);
     if (v > 0) return v;
   }
-  static int cached = 0;
-  if (cached == 0) {
-    int dev = 0;
+  // per device, filled on first use (a race between threads only repeats the query)
+  static std::atomic<int> cached[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return -1;
+  if (dev < 0 || dev >= kMaxDevices) dev = 0;
+  int v = cached[dev].load(std::memory_order_relaxed);
+  if (v == 0) {
     hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
-      cached = prop.multiProcessorCount;
-    else
-      cached = -1;
+    v = hipGetDeviceProperties(&prop, dev) == hipSuccess ? prop.multiProcessorCount : -1;
+    cached[dev].store(v, std::memory_order_relaxed);
   }
-  return cached;
+  return v;
 }
 
 }  // namespace
@@ -710,12 +714,15 @@ hipError_t launch_gemm(const GemmParams& p_in, bool debug, hipStream_t st) {
   p.main_tj = plan.main_tj;
   p.tail_tj = plan.tail_tj;
   const int grid = plan.n_main + p.nib * plan.tail_tj;
-  static bool attr_set = false;
-  if (!attr_set) {
+  // the kernel needs more dynamic LDS than the default limit: raise it once per device
+  static std::atomic<bool> attr_set[kMaxDevices];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) dev = 0;
+  if (!attr_set[dev].load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
-    attr_set = true;
+    attr_set[dev].store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(gemm_kernel, dim3(grid), dim3(kThreads), kLdsBytes, st, p);
   return hipGetLastError();
