@@ -161,7 +161,7 @@ def criteria(args):
 
 
 def sweep(args):
-    """BASELINE config 5: M = K = N = 8192, fallback fraction and placement swept."""
+    """Workload config 5 (the square problem): M = K = N = 8192, fallback fraction and placement swept."""
     import torch
     import paper_2503_08040_amd as fq
     from paper_2503_08040_amd import synth

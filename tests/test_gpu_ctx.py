@@ -82,7 +82,7 @@ def test_ctx_strided_input_and_output():
 
 
 def test_ctx_glu_activation_shape():
-    """The up/gate activation of BASELINE config 3 (what a SiLU-GLU layer would keep), a slice the
+    """The up/gate activation of workload config 3 (what a SiLU-GLU layer would keep), a slice the
     oracle finishes quickly, plus the 5/8 size claim of Sec. 5.2 on the full shape."""
     wl = synth.config3()
     bits = np.ascontiguousarray(wl.X[:192])

@@ -227,7 +227,7 @@ def _sampled_windows(rng, Mo, No, flagged_rows, n=24, h=4, w=8):
 
 @pytest.mark.parametrize("cfg", ["cfg2", "cfg3", "cfg5_random", "cfg5_sequential"])
 def test_full_size_sampled(cfg, monkeypatch):
-    """BASELINE configs 2, 3 and 5 at full size, in the launch configuration the
+    """Workload configs 2, 3 and 5 at full size, in the launch configuration the
     benchmark times: quantizer outputs bit-exact in full, GEMM outputs compared
     on sampled windows the oracle computes element by element (windows cover
     every kind of row: with flagged blocks, without, first and last tile)."""
