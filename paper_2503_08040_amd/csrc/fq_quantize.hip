@@ -54,13 +54,6 @@ __device__ inline void block_sum2(double& a, double& b, double* red) {
   b = (red[4] + red[5]) + (red[6] + red[7]);
 }
 
-// round-to-nearest-even of the correctly rounded quotient x/a (r = fast_recip(a)), clamped.
-__device__ inline int quantize_one(float x, float a, float r) {
-  float t = rint_quotient(x, a, r);
-  t = fminf(fmaxf(t, -127.0f), 127.0f);
-  return (int)t;
-}
-
 // Philox4x32-10 (Salmon et al., SC'11): counter (c0, c1, 0, 0), key (k0, k1).
 __device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1,
                                      uint32_t (&out)[4]) {
@@ -110,6 +103,20 @@ __device__ inline int code_at(const v4i (&q)[4], int pz, int e) {
 __device__ __forceinline__ void forget_unpacked(v4i (&raw)[4][2]) {
 #pragma unroll
   for (int pz = 0; pz < 4; ++pz) asm volatile("" : "+v"(raw[pz][0]), "+v"(raw[pz][1]));
+}
+
+// Round-to-nearest codes are packed without leaving the float domain: k is an integer-valued
+// float in [-127, 127] (rint of a quotient whose magnitude cannot exceed 127 by more than a few
+// ulp, so no clamp is needed), k + 128 is exact and lies in [1, 255], and the pack-to-byte
+// conversion drops it into byte e % 4 of the row's dword.  finish_codes then turns the four
+// bytes of each dword into two's complement: k + 128 and k mod 256 differ in bit 7 only.
+__device__ __forceinline__ void put_code_f(v4i& q, int e, float k) {
+  q[e >> 2] = (int)__builtin_amdgcn_cvt_pk_u8_f32(k + 128.0f, e & 3,
+                                                  (e & 3) ? (unsigned)q[e >> 2] : 0u);
+}
+__device__ __forceinline__ void finish_codes(v4i& q) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) q[d] ^= (int)0x80808080u;
 }
 
 __device__ inline void put_code(v4i& q, int e, int code) {
@@ -252,10 +259,11 @@ void quantize_kernel(QuantParams p) {
     for (int pz = 0; pz < 4; ++pz) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        put_code(q[pz], e, (a == 0.0f) ? 0 : quantize_one(x_at(raw, pz, e), a, a_rcp));
-        // eight divisions in flight at a time: bounds the live temporaries
+        put_code_f(q[pz], e, (a == 0.0f) ? 0.0f : rint_quotient(x_at(raw, pz, e), a, a_rcp));
+        // eight elements in flight at a time: bounds the live temporaries
         if ((e & 7) == 7) __builtin_amdgcn_sched_barrier(0);
       }
+      finish_codes(q[pz]);
     }
   } else {
     // element (r, c) uses word (r*cols + c) & 3 of the Philox block with counter (r*cols + c) >> 2.
@@ -352,9 +360,10 @@ void quantize_kernel(QuantParams p) {
   for (int pz = 0; pz < 4; ++pz) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      put_code(rq[pz], e, (ra == 0.0f) ? 0 : quantize_one(residual(pz, e), ra, ra_rcp));
+      put_code_f(rq[pz], e, (ra == 0.0f) ? 0.0f : rint_quotient(residual(pz, e), ra, ra_rcp));
       if ((e & 7) == 7) __builtin_amdgcn_sched_barrier(0);
     }
+    finish_codes(rq[pz]);
   }
 
   int8_t* rdst = p.res_codes + (int64_t)slot * kBlockBytes;
