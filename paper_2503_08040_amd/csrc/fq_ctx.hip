@@ -340,19 +340,33 @@ __global__ __launch_bounds__(kCtxThreads) void rmsnorm_dx_dw_kernel(RmsParams p)
     if (q0.c0 + i < p.cols) dst[i] = dwacc[i];
 }
 
-// dw[c] = sum of the partial sums: four interleaved slices of parts per column, each added in
-// part order, then the four slice sums in slice order (deterministic).
-__global__ __launch_bounds__(256) void rmsnorm_dw_kernel(const float* parts, int n_parts, int cols,
-                                                         float* dw) {
-  __shared__ float red[4][64];
-  const int c = blockIdx.x * 64 + (threadIdx.x & 63), k = threadIdx.x >> 6;
-  float s = 0.0f;
-  if (c < cols)
-    for (int i = k; i < n_parts; i += 4) s += parts[(int64_t)i * cols + c];
-  red[k][threadIdx.x & 63] = s;
+// dw[c] = sum of the partial sums, in a fixed order: thread (slice k of 16, column c) adds the
+// parts k, k + 16, k + 32, ... into eight interleaved running sums (eight loads in flight), folds
+// them pairwise, and the sixteen slice sums of a column are folded pairwise in slice order.
+constexpr int kDwCols = 32, kDwSlices = 16;
+__global__ __launch_bounds__(kDwCols * kDwSlices) void rmsnorm_dw_kernel(const float* parts, int n_parts,
+                                                                      int cols, float* dw) {
+  __shared__ float red[kDwSlices][kDwCols];
+  const int lc = threadIdx.x % kDwCols, k = threadIdx.x / kDwCols;
+  const int c = blockIdx.x * kDwCols + lc;
+  float s[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+  if (c < cols) {
+    int i = k;
+    for (; i + 7 * kDwSlices < n_parts; i += 8 * kDwSlices) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) s[j] += parts[(int64_t)(i + j * kDwSlices) * cols + c];
+    }
+#pragma unroll
+    for (int j = 0; j < 7; ++j)     // at most seven parts are left for this slice
+      if (i + j * kDwSlices < n_parts) s[j] += parts[(int64_t)(i + j * kDwSlices) * cols + c];
+  }
+  red[k][lc] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
   __syncthreads();
-  if (k == 0 && c < cols)
-    dw[c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+  for (int half = kDwSlices / 2; half > 0; half >>= 1) {
+    if (k < half) red[k][lc] += red[k + half][lc];
+    __syncthreads();
+  }
+  if (k == 0 && c < cols) dw[c] = red[0][lc];
 }
 
 }  // namespace
@@ -374,7 +388,8 @@ hipError_t launch_rmsnorm(const RmsParams& p, bool backward, hipStream_t st) {
     hipLaunchKernelGGL(rmsnorm_dx_dw_kernel, dim3((unsigned)chunks, (unsigned)p.n_parts),
                        dim3(kCtxThreads), 0, st, p);
   }
-  hipLaunchKernelGGL(rmsnorm_dw_kernel, dim3((unsigned)((p.cols + 63) / 64)), dim3(256), 0, st, p.dw_parts,
+  hipLaunchKernelGGL(rmsnorm_dw_kernel, dim3((unsigned)((p.cols + kDwCols - 1) / kDwCols)),
+                     dim3(kDwCols * kDwSlices), 0, st, p.dw_parts,
                      n_parts, p.cols, p.dw);
   return hipGetLastError();
 }
