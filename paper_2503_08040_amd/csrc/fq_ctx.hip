@@ -116,17 +116,25 @@ __device__ inline void quantize_store(const float (&x)[kValsPerLane], const Lane
   const float a = __fdiv_rn(amax, 511.0f);
   const float a_rcp = fast_recip(a);
 
+  // The rounded quotient k lies in [-511, 511] (rint_quotient clamps where a clamp can matter).
+  // k + 512 is a positive 10-bit number that differs from k's
+  // two's-complement field in bit 9 only: the fields are assembled from it without masking and
+  // one XOR per dword flips the sixteen sign bits at the end (0x200 repeated every 10 bits).
   uint32_t w[5] = {0, 0, 0, 0, 0};
   if (a != 0.0f) {
 #pragma unroll
     for (int i = 0; i < kValsPerLane; ++i) {
-      float t = rint_quotient(x[i], a, a_rcp);
-      t = fminf(fmaxf(t, -511.0f), 511.0f);
-      const uint32_t bits = (uint32_t)(int)t & 0x3FFu;
+      const uint32_t bits = (uint32_t)(rint_quotient(x[i], a, a_rcp, 511.0f) + 512.0f);
       const int pos = 10 * i, word = pos >> 5, sh = pos & 31;
       w[word] |= bits << sh;
       if (sh > 22) w[word + 1] |= bits >> (32 - sh);
     }
+    // bit 9 of field i is bit 10 i + 9 of the 160-bit record
+    w[0] ^= 0x20080200u;
+    w[1] ^= 0x08020080u;
+    w[2] ^= 0x02008020u;
+    w[3] ^= 0x00802008u;
+    w[4] ^= 0x80200802u;
   }
   if (!q.live) return;
   uint32_t* dst = reinterpret_cast<uint32_t*>(packed + q.g * kCtxGroupBytes) + q.s * 5;

@@ -27,13 +27,18 @@ __device__ inline uint32_t float_to_bf16_bits(float f) {
   return (w + 0x7FFFu + ((w >> 16) & 1u)) >> 16;
 }
 
-// round-to-nearest-even of the correctly rounded binary32 quotient x / a, for |x / a| <= ~512,
-// without dividing in the common case.  With r = fast_recip(a) (an approximate reciprocal: 1 ulp
-// by specification, 4 ulp are allowed for here) the product x * r differs from the true
-// quotient by less than 2^-11 and the rounded quotient differs from it by less than 2^-15, so
-// whenever x * r is farther than kTieGuard = 2^-10 from a half-integer, both round to the same
-// integer.  Otherwise (about two elements in a thousand, or r = NaN) the quotient is formed
-// exactly.  The result equals rintf(x / a) in IEEE arithmetic for every input.
+// round-to-nearest-even of the correctly rounded binary32 quotient x / a, clamped to +-lim, where
+// a = max|x| / lim over a set that contains x (lim = 127 or 511), without dividing in the common
+// case.  With r = fast_recip(a) (an approximate reciprocal: 1 ulp by specification, 4 ulp are
+// allowed for here) the product x * r differs from the true quotient by less than 2^-11 and the
+// rounded quotient differs from it by less than 2^-15, so whenever x * r is farther than
+// kTieGuard = 2^-10 from a half-integer, both round to the same integer.  Otherwise (about two
+// elements in a thousand, or r = NaN) the quotient is formed exactly.
+// The clamp is needed only when a is subnormal: a normal a is within 2^-24 (relative) of
+// max|x| / lim, so |x / a| <= lim (1 + 2^-23) rounds to at most lim, while a subnormal a can be off
+// by half a unit of 2^-149 and the quotient can then exceed lim by far.  fast_recip returns NaN
+// for such scales, which sends every element down the exact path, where the clamp is.
+// The result equals min(max(rintf(x / a), -lim), lim) in IEEE arithmetic for every finite input.
 constexpr float kTieGuard = 0x1p-10f;
 
 // Reciprocal for rint_quotient; NaN (which sends every element down the exact path) when a is
@@ -42,10 +47,10 @@ __device__ inline float fast_recip(float a) {
   return (a >= 0x1p-100f && a <= 0x1p100f) ? __builtin_amdgcn_rcpf(a) : __int_as_float(0x7FC00000);
 }
 
-__device__ inline float rint_quotient(float x, float a, float r) {
+__device__ inline float rint_quotient(float x, float a, float r, float lim) {
   const float tp = x * r;
   float k = rintf(tp);
-  if (!(fabsf(tp - k) < 0.5f - kTieGuard)) k = rintf(__fdiv_rn(x, a));
+  if (!(fabsf(tp - k) < 0.5f - kTieGuard)) k = fminf(fmaxf(rintf(__fdiv_rn(x, a)), -lim), lim);
   return k;
 }
 

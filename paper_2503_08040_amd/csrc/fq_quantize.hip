@@ -106,8 +106,7 @@ __device__ __forceinline__ void forget_unpacked(v4i (&raw)[4][2]) {
 }
 
 // Round-to-nearest codes are packed without leaving the float domain: k is an integer-valued
-// float in [-127, 127] (rint of a quotient whose magnitude cannot exceed 127 by more than a few
-// ulp, so no clamp is needed), k + 128 is exact and lies in [1, 255], and the pack-to-byte
+// float in [-127, 127] (rint_quotient clamps where a clamp can matter), k + 128 is exact and lies in [1, 255], and the pack-to-byte
 // conversion drops it into byte e % 4 of the row's dword.  finish_codes then turns the four
 // bytes of each dword into two's complement: k + 128 and k mod 256 differ in bit 7 only.
 __device__ __forceinline__ void put_code_f(v4i& q, int e, float k) {
@@ -259,7 +258,7 @@ void quantize_kernel(QuantParams p) {
     for (int pz = 0; pz < 4; ++pz) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        put_code_f(q[pz], e, (a == 0.0f) ? 0.0f : rint_quotient(x_at(raw, pz, e), a, a_rcp));
+        put_code_f(q[pz], e, (a == 0.0f) ? 0.0f : rint_quotient(x_at(raw, pz, e), a, a_rcp, 127.0f));
         // eight elements in flight at a time: bounds the live temporaries
         if ((e & 7) == 7) __builtin_amdgcn_sched_barrier(0);
       }
@@ -360,7 +359,7 @@ void quantize_kernel(QuantParams p) {
   for (int pz = 0; pz < 4; ++pz) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
-      put_code_f(rq[pz], e, (ra == 0.0f) ? 0.0f : rint_quotient(residual(pz, e), ra, ra_rcp));
+      put_code_f(rq[pz], e, (ra == 0.0f) ? 0.0f : rint_quotient(residual(pz, e), ra, ra_rcp, 127.0f));
       if ((e & 7) == 7) __builtin_amdgcn_sched_barrier(0);
     }
     finish_codes(rq[pz]);

@@ -78,6 +78,25 @@ def test_threshold_edge_cases_and_special_values():
     assert oq.scales[0, 0] == F32(2.0 ** -133)
 
 
+def test_subnormal_scales_need_the_clamp():
+    """bf16 subnormals m * 2^-133: scales and residual scales are subnormal binary32 numbers, whole
+    multiples of 2^-149 and therefore far from max/127, so quotients leave the code range and are
+    clamped (the hand-worked oracle pin, tiled over blocks, plus random subnormal blocks)."""
+    rng = np.random.default_rng(12)
+    pat = np.array([[3, 1], [1 | 0x8000, 0]], dtype=np.uint16)          # bit patterns: m, sign
+    bits = np.tile(pat, (128, 128)).astype(np.uint16)                   # 256 x 256
+    rnd = rng.integers(0, 128, size=(128, 256)).astype(np.uint16)
+    bits[128:, :] = rnd | (rng.integers(0, 2, size=(128, 256)).astype(np.uint16) << 15)
+    gq, oq = _run(bits, fq.FQ_CRIT_ALL, 0.0, label="subnormal clamp")
+    assert oq.res_codes.min() == -127 and oq.res_codes.max() == 127
+    assert oq.res_scales[0, 0] == F32(4 * 2.0 ** -149)
+    # the INT10 context quantizer meets the same situation (a = max / 511)
+    packed, scales = fq.fq_ctx_quantize(gu.to_device_bf16(bits))
+    o_packed, o_scales = fqo.ctx_quantize(bits)
+    assert np.array_equal(packed.cpu().numpy(), o_packed)
+    assert np.array_equal(scales.cpu().numpy().view(np.uint32), o_scales.view(np.uint32))
+
+
 def test_rounding_ties_on_gpu():
     """Every block holds exact ties k + 0.5 (a = 1): the GPU must round to even."""
     x = np.zeros((128, 256), F32)

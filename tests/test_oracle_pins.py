@@ -185,6 +185,20 @@ def _int_blocks(rng, rows, cols, g):
     return x
 
 
+def test_clamp_matters_for_subnormal_scales():
+    """Worked by hand in units of u = 2^-149 (Sec. 3.1, 4.3): the block [[3, 1], [-1, 0]] * 2^-133
+    has a = RN(196608 u / 127) = 1548 u, codes [[127, 42], [-42, 0]], residuals
+    [[12, 520], [-520, 0]] u and a~ = RN(520 u / 127) = 4 u: a subnormal scale is an integer number
+    of u, far from 520/127, so r / a~ = +-130 lies outside the code range and is clamped to +-127."""
+    u = 2.0 ** -149
+    x = np.array([[3.0, 1.0], [-1.0, 0.0]]) * 2.0 ** -133
+    q = fqo.quantize(synth.to_bf16_bits(x.astype(F32)), 2, fqo.CRIT_ALL, 0.0)
+    assert float(q.scales[0, 0]) == 1548 * u
+    assert q.codes.tolist() == [[127, 42], [-42, 0]]
+    assert float(q.res_scales[0, 0]) == 4 * u
+    assert q.res_codes.tolist() == [[3, 127], [-127, 0]]
+
+
 @pytest.mark.parametrize("op", [fqo.OP_NT, fqo.OP_NN, fqo.OP_TN])
 def test_integer_inputs_reduce_to_integer_matmul(op):
     """All scales 1 -> Eq. (1) is an exact integer matrix product (numpy int64)."""
