@@ -97,6 +97,31 @@ def test_subnormal_scales_need_the_clamp():
     assert np.array_equal(scales.cpu().numpy().view(np.uint32), o_scales.view(np.uint32))
 
 
+def test_extreme_magnitudes():
+    """Blocks scaled by 2^k from the subnormal range up to just below the largest finite bf16:
+    every code path that treats small and large scales differently (the reciprocal shortcut is
+    only taken for scales in [2^-100, 2^100]) must still agree with the oracle bit for bit, for
+    nearest and stochastic rounding and for the INT10 contexts."""
+    rng = np.random.default_rng(33)
+    ks = [-140, -133, -127, -126, -110, -101, -100, -99, -90, -20, 0, 60, 99, 100, 101, 110, 120, 126]
+    x = np.zeros((3 * 128, 6 * 128), np.float64)
+    for b, k in enumerate(ks):
+        bi, bk = divmod(b, 6)
+        blk = rng.standard_normal((128, 128)) * 2.0 ** k
+        blk[rng.integers(128), rng.integers(128)] = 1.9 * 2.0 ** k
+        x[bi * 128:(bi + 1) * 128, bk * 128:(bk + 1) * 128] = blk
+    x = np.clip(x, -3.0e38, 3.0e38)
+    with np.errstate(under="ignore"):
+        bits = synth.to_bf16_bits(x.astype(F32))
+    _run(bits, fq.FQ_CRIT_ALL, 0.0, label="extreme magnitudes")
+    gq = fq.fq_quantize_sr(gu.to_device_bf16(bits), 99, want_transposed=True)
+    gu.compare_quantized(gq, fqo.quantize_sr(bits, 128, 99), "extreme magnitudes, stochastic")
+    packed, scales = fq.fq_ctx_quantize(gu.to_device_bf16(bits))
+    o_packed, o_scales = fqo.ctx_quantize(bits)
+    assert np.array_equal(packed.cpu().numpy(), o_packed)
+    assert np.array_equal(scales.cpu().numpy().view(np.uint32), o_scales.view(np.uint32))
+
+
 def test_rounding_ties_on_gpu():
     """Every block holds exact ties k + 0.5 (a = 1): the GPU must round to even."""
     x = np.zeros((128, 256), F32)
