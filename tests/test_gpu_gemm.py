@@ -138,6 +138,26 @@ def test_mixed_tile_geometries(op, sa, sb, cus, monkeypatch):
     assert np.array_equal(fq.fq_gemm(op, ga, gb).cpu().numpy(), c)
 
 
+def test_scale_products_in_the_subnormal_range():
+    """A and B blocks so small that a^A * a^B is subnormal or underflows to zero: the product of
+    the scales, the FMA with it and the accumulator must behave as IEEE binary32 without
+    flush-to-zero on both sides."""
+    rng = np.random.default_rng(44)
+    a = rng.standard_normal((256, 512))
+    for bk, k in enumerate((-126, -118, -110, -104)):
+        a[:, bk * 128:(bk + 1) * 128] *= 2.0 ** k
+    a[5, 3] = 50.0 * 2.0 ** -126                      # an outlier among tiny values
+    b = rng.standard_normal((384, 512)) * 2.0 ** -24
+    b[:128] *= 2.0 ** -20
+    with np.errstate(under="ignore"):
+        ab, bb = synth.to_bf16_bits(a.astype(F32)), synth.to_bf16_bits(b.astype(F32))
+    ga, gb, oa, ob = _quant_pair(ab, bb, fq.FQ_CRIT_ALL, 0.0)
+    c = _check_gemm(fq.FQ_OP_NT, ga, gb, oa, ob, "tiny scales", partials=False)
+    assert np.isfinite(c).all()
+    sub = (c != 0) & (np.abs(c) < 2.0 ** -126)
+    assert sub.mean() > 0.1                            # subnormal outputs were produced and kept
+
+
 def test_strided_output_and_reuse():
     wl = synth.config1()
     ga, gb, oa, ob = _quant_pair(wl.X, wl.W, fq.FQ_CRIT_ABSMAX_GT, wl.theta)
