@@ -23,7 +23,10 @@ def _matrix(rng, shape, heavy):
         x.flat[rng.integers(0, x.size, size=n)] *= F32(rng.uniform(30, 300))
     if rng.random() < 0.3:
         x[:, rng.integers(0, shape[1])] = 0.0
-    return synth.to_bf16_bits(x)
+    if rng.random() < 0.15:          # down into the subnormal range: scales far from max/127
+        x = x * F32(2.0 ** -126) / max(F32(1.0), np.abs(x).max() / F32(64.0))
+    with np.errstate(under="ignore"):
+        return synth.to_bf16_bits(x)
 
 
 import os
