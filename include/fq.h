@@ -160,6 +160,12 @@ fq_status fq_qtensor_bind(void *base, int32_t rows, int32_t cols, int32_t block,
  * Errors: FQ_ERR_NULL, FQ_ERR_SHAPE (rows/cols < 0, ld < cols), FQ_ERR_BLOCK,
  * FQ_ERR_ENUM, FQ_ERR_CAPACITY (capacity 0 with a fallback criterion),
  * FQ_ERR_HIP.  rows == 0 or cols == 0 is valid and only zeroes fb_count.
+ * Stream capture: the call may be recorded into a HIP graph (it launches kernels only, no
+ * memset); the recorded form clears the tensor's slot counters itself, so the graph can be
+ * replayed any number of times.  A tensor quantized under capture should afterwards be written
+ * through replays of that graph only: a quantize call outside the graph between two replays
+ * leaves the counters in a state the next such call does not expect (re-bind the tensor with
+ * fq_qtensor_bind to use it outside the graph again).
  */
 fq_status fq_quantize(const void *x_bf16, int32_t rows, int32_t cols, int64_t ld,
                       int32_t block, fq_criterion crit, float theta, fq_qtensor *out,

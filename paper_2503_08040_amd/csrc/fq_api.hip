@@ -162,13 +162,21 @@ fq_status quantize_impl(const void* x_bf16, int32_t rows, int32_t cols, int64_t 
   p.codes = out->codes; p.codes_t = out->codes_t;
   p.scales = out->scales; p.mask = out->mask;
   // Two alternating counters: this call counts in one and clears the other for the next call.
-  const bool first = out->epoch == 0;
-  const int live = out->epoch & 1;
+  // Under stream capture the launches are replayed without passing through here again, so the
+  // recorded form must not depend on which counter is clean: it clears both first and counts in
+  // counter 0, and the tensor is marked as fresh for the next call that is not captured.
+  hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+  const bool capturing =
+      hipStreamIsCapturing(static_cast<hipStream_t>(hip_stream), &capture) == hipSuccess &&
+      capture == hipStreamCaptureStatusActive;
+  const bool first = out->epoch == 0 || capturing;
+  const int live = capturing ? 0 : (out->epoch & 1);
   p.fb_count = out->fb_counters + live;
   p.fb_count_next = out->fb_counters + (live ^ 1);
   p.clear_both = (first || empty) ? 1 : 0;
   out->fb_count = empty ? out->fb_counters : p.fb_count;
-  out->epoch = empty ? 2 : (out->epoch >= (1 << 30) ? 2 + (live ^ 1) : out->epoch + 1);
+  if (capturing) out->epoch = 0;
+  else out->epoch = empty ? 2 : (out->epoch >= (1 << 30) ? 2 + (live ^ 1) : out->epoch + 1);
   p.fb_list = out->fb_list; p.fb_slot = out->fb_slot;
   p.res_codes = out->res_codes; p.res_codes_t = out->res_codes_t; p.res_scales = out->res_scales;
   out->criterion = (int32_t)crit;
