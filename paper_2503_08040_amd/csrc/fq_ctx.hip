@@ -83,6 +83,33 @@ __device__ inline void load16(const uint16_t* src, bool live, bool vec, int c0, 
   }
 }
 
+// The same 16 values left in their packed form (two per dword, low half first), and the unpacking.
+__device__ inline void load16_raw(const uint16_t* src, bool live, bool vec, int c0, int cols,
+                                  v4u (&raw)[2]) {
+  if (live && vec && c0 + kValsPerLane <= cols) {
+    const v4u* v = reinterpret_cast<const v4u*>(src);
+    raw[0] = v[0];
+    raw[1] = v[1];
+  } else {
+#pragma unroll
+    for (int d = 0; d < 8; ++d) {
+      uint32_t wd = 0;
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh)
+        if (live && c0 + 2 * d + hh < cols) wd |= (uint32_t)src[2 * d + hh] << (16 * hh);
+      raw[d >> 2][d & 3] = wd;
+    }
+  }
+}
+
+__device__ inline void unpack16(const v4u (&raw)[2], float (&x)[kValsPerLane]) {
+#pragma unroll
+  for (int d = 0; d < 8; ++d) {
+    x[2 * d] = __uint_as_float(raw[d >> 2][d & 3] << 16);
+    x[2 * d + 1] = __uint_as_float(raw[d >> 2][d & 3] & 0xFFFF0000u);
+  }
+}
+
 // 16 floats -> 16 consecutive bf16 values of a row (round-to-nearest-even).
 __device__ inline void store16(uint16_t* dst, bool vec, int c0, int cols,
                                const float (&v)[kValsPerLane]) {
@@ -252,25 +279,37 @@ __global__ __launch_bounds__(kCtxThreads) void rmsnorm_forward_kernel(RmsParams 
   __shared__ float red[4];
   const int64_t r = blockIdx.x;
   const int chunks = (p.ng + kRowChunkGroups - 1) / kRowChunkGroups;
-  float xc[kCache ? kRmsMaxChunks : 1][kValsPerLane];
+  // the cached row stays in the packed form it was loaded in (half the registers of floats)
+  v4u xraw[kCache ? kRmsMaxChunks : 1][2];
+  float xc[kValsPerLane];
   float ss = 0.0f;
   if (kCache) {
 #pragma unroll
     for (int ch = 0; ch < kRmsMaxChunks; ++ch) {
       const LanePos q = row_pos(r, ch, p.ng);
-      load16(p.x + r * p.ld + q.c0, q.live && ch < chunks, p.vec_ok, q.c0, p.cols, xc[ch]);
+      load16_raw(p.x + r * p.ld + q.c0, q.live && ch < chunks, p.vec_ok, q.c0, p.cols, xraw[ch]);
+    }
 #pragma unroll
-      for (int i = 0; i < kValsPerLane; ++i) ss = __builtin_fmaf(xc[ch][i], xc[ch][i], ss);
+    for (int ch = 0; ch < kRmsMaxChunks; ++ch) {
+      unpack16(xraw[ch], xc);
+#pragma unroll
+      for (int i = 0; i < kValsPerLane; ++i) ss = __builtin_fmaf(xc[i], xc[i], ss);
     }
   } else {
     for (int ch = 0; ch < chunks; ++ch) {
       const LanePos q = row_pos(r, ch, p.ng);
-      load16(p.x + r * p.ld + q.c0, q.live, p.vec_ok, q.c0, p.cols, xc[0]);
+      load16(p.x + r * p.ld + q.c0, q.live, p.vec_ok, q.c0, p.cols, xc);
 #pragma unroll
-      for (int i = 0; i < kValsPerLane; ++i) ss = __builtin_fmaf(xc[0][i], xc[0][i], ss);
+      for (int i = 0; i < kValsPerLane; ++i) ss = __builtin_fmaf(xc[i], xc[i], ss);
     }
   }
   ss = block_sum(ss, red);
+  if (kCache) {
+    // keep only the packed row across the reduction: the floats are cheap to unpack again
+#pragma unroll
+    for (int ch = 0; ch < kRmsMaxChunks; ++ch)
+      asm volatile("" : "+v"(xraw[ch][0]), "+v"(xraw[ch][1]));
+  }
   const float rstd = __fdiv_rn(1.0f, __fsqrt_rn(__fdiv_rn(ss, (float)p.cols) + p.eps));
   if (threadIdx.x == 0) p.rstd[r] = rstd;
   auto finish = [&](int ch, const float (&x)[kValsPerLane]) {
@@ -285,12 +324,15 @@ __global__ __launch_bounds__(kCtxThreads) void rmsnorm_forward_kernel(RmsParams 
   if (kCache) {
 #pragma unroll
     for (int ch = 0; ch < kRmsMaxChunks; ++ch)
-      if (ch < chunks) finish(ch, xc[ch]);      // uniform over the workgroup
+      if (ch < chunks) {                        // uniform over the workgroup
+        unpack16(xraw[ch], xc);
+        finish(ch, xc);
+      }
   } else {
     for (int ch = 0; ch < chunks; ++ch) {
       const LanePos q = row_pos(r, ch, p.ng);
-      load16(p.x + r * p.ld + q.c0, q.live, p.vec_ok, q.c0, p.cols, xc[0]);
-      finish(ch, xc[0]);
+      load16(p.x + r * p.ld + q.c0, q.live, p.vec_ok, q.c0, p.cols, xc);
+      finish(ch, xc);
     }
   }
 }
