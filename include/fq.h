@@ -15,9 +15,9 @@
  * General rules
  *   - Every data pointer is caller-owned DEVICE memory (hipMalloc'ed or a
  *     PyTorch CUDA/HIP tensor's storage) unless a comment says "host".  The
- *     library never allocates, frees or retains device memory and keeps no
- *     hidden state: all that is carried from one call to the next lives in the
- *     caller's fq_qtensor (its `epoch` field and `fb_counters` buffer).
+ *     library never allocates, frees or retains device memory: all that is
+ *     carried from one call to the next lives in the caller's fq_qtensor (its
+ *     `epoch` field and `fb_counters` buffer).
  *     fq_qtensor structs themselves live in host memory.
  *   - Calls enqueue kernels on `hip_stream` (a hipStream_t passed as void*;
  *     NULL is the default stream) and return without waiting.
@@ -25,6 +25,13 @@
  *     failed validation returns a negative fq_status and launches nothing.
  *     HIP launch failures are returned as FQ_ERR_HIP.  No exception crosses
  *     this boundary.
+ *   - Threads and streams: calls on different tensors and buffers may run concurrently from
+ *     any threads and on any streams.  Calls that write the same fq_qtensor (its struct is
+ *     updated on the host and its buffers on the device) or the same output buffer must be
+ *     ordered by the caller, and a tensor must not be consumed (fq_gemm, fq_qtensor_check) on a
+ *     stream that is not ordered after the quantize call that filled it.  The only state the
+ *     library keeps by itself is a per-device cache of the compute-unit count and of a kernel
+ *     attribute, both written once and safe to race on.
  *   - The quantization block is 128 x 128 (FQ_BLOCK); other sizes return
  *     FQ_ERR_BLOCK.  Matrix dimensions need not be multiples of 128: an edge
  *     block consists of the elements that exist, the rest counts as zero.
