@@ -116,7 +116,8 @@ typedef struct {
   int32_t capacity;      /* number of residual slots the res_* buffers hold      */
   int32_t criterion;     /* host: fq_criterion of the last fq_quantize into this */
   int32_t epoch;         /* host: fq_quantize calls made into this tensor (library-managed;
-                            fq_qtensor_bind sets 0; selects the live counter)         */
+                            fq_qtensor_bind sets 0; selects the live counter; -1 once a
+                            call into the tensor has been recorded under stream capture) */
   int8_t *codes;         /* [nbr*nbc][16384] tile order, Q^(G)        (Sec. 3.1) */
   int8_t *codes_t;       /* [nbc*nbr][16384] tile order of G^T, or NULL          */
   float *scales;         /* [nbr, nbc]  a_{i,k} = max|G_ik| / 127     (Sec. 3.1) */
@@ -124,12 +125,14 @@ typedef struct {
   int32_t *fb_count;     /* [1]  number of flagged blocks (may exceed capacity).
                             Points at one of the two fb_counters; fq_quantize
                             re-points it on every call                           */
-  int32_t *fb_counters;  /* [2]  the two alternating slot counters: a call counts
-                            in one and clears the other for the next call, so the
-                            quantizer is a single kernel launch                  */
-  int32_t *fb_list;      /* [capacity] compact list of flagged blocks in slot order:
-                            fb_list[s] = bi*nbc+bk of the block in slot s, for
-                            s < min(fb_count, capacity); the rest is unspecified */
+  int32_t *fb_counters;  /* [3]  library-managed: two alternating slot counters (a call
+                            counts in one and clears the other for the next call, so the
+                            quantizer is a single kernel launch) and a counter of the
+                            workgroups that have finished their block               */
+  int32_t *fb_list;      /* [capacity] ascending list of the flagged blocks' ids bi*nbc+bk
+                            (the first min(fb_count, capacity) entries are valid; when more
+                            blocks are flagged than `capacity`, the lowest `capacity` ids);
+                            deterministic: it does not depend on the slot assignment  */
   int32_t *fb_slot;      /* [nbr, nbc] residual slot of the block, -1 if not
                             flagged, -2 if flagged but no slot was left. Slots
                             are a bijection onto [0, fb_count) in no fixed order */
@@ -160,6 +163,7 @@ fq_status fq_qtensor_bind(void *base, int32_t rows, int32_t cols, int32_t block,
  * Outputs: every buffer of `out` that is not NULL-optional (codes, scales,
  * mask, fb_count, fb_list, fb_slot; res_* when capacity > 0; *_t when set).
  * The first call into a freshly bound tensor also clears fb_counters.
+ * fb_list is written by the workgroup that finishes last, from the flags of all blocks.
  * out->capacity may be 0 only with FQ_CRIT_NONE.  If more blocks are flagged
  * than there are slots, the surplus blocks get fb_slot = -2, fb_count still
  * reports the true count, and any fq_gemm using the tensor as A writes NaN to
@@ -168,11 +172,10 @@ fq_status fq_qtensor_bind(void *base, int32_t rows, int32_t cols, int32_t block,
  * FQ_ERR_ENUM, FQ_ERR_CAPACITY (capacity 0 with a fallback criterion),
  * FQ_ERR_HIP.  rows == 0 or cols == 0 is valid and only zeroes fb_count.
  * Stream capture: the call may be recorded into a HIP graph (it launches kernels only, no
- * memset); the recorded form clears the tensor's slot counters itself, so the graph can be
- * replayed any number of times.  A tensor quantized under capture should afterwards be written
- * through replays of that graph only: a quantize call outside the graph between two replays
- * leaves the counters in a state the next such call does not expect (re-bind the tensor with
- * fq_qtensor_bind to use it outside the graph again).
+ * memset); the recorded form clears the tensor's counters itself, so the graph can be
+ * replayed any number of times.  Once a call into a tensor has been captured, every later call
+ * into it (eager calls between replays included) takes that two-launch form as well, so eager
+ * calls and replays may be mixed freely; fq_qtensor_bind resets this.
  */
 fq_status fq_quantize(const void *x_bf16, int32_t rows, int32_t cols, int64_t ld,
                       int32_t block, fq_criterion crit, float theta, fq_qtensor *out,

@@ -26,10 +26,12 @@
  *                                                          : Sec. 3.2
  *
  * Arithmetic: the paper fixes INT8 codes, INT32 block products and an FP32
- * accumulator.  It does not fix the precision in which a code is decided, so
- * the decision is taken in IEEE binary32 (the precision the GPU kernel
- * decides in), one operation at a time, round-to-nearest-even, no contraction
- * (build with -ffp-contract=off), no flush-to-zero:
+ * accumulator.  It does not fix the precision in which a code is decided.
+ * Reading taken here: Sec. 3.1 prints a = max|G| / L and round(G / a) as two
+ * operations on scale factors it stores in full precision next to bf16 data,
+ * so each printed operation is one IEEE binary32 operation (the inputs widen
+ * to binary32 exactly), round-to-nearest-even, no contraction (build with
+ * -ffp-contract=off), no flush-to-zero:
  *     a  = amax / 127.0f            one division
  *     q  = clamp(rintf(x / a))      one division, one rounding, clamp +-127
  *     r  = fmaf(-(float)q, a, x)    residual, single rounding

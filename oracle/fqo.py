@@ -163,6 +163,26 @@ def gemm(op, A: QTensor, B: QTensor, window=None, want_bf16=False, a_fallback=Tr
     return (c, cb) if want_bf16 else c
 
 
+def gemm_window(op, A: QTensor, B: QTensor, window, want_bf16=False):
+    """Alg. 1 on the window (i0, i1, j0, j1) of the output, returning only the window's rows
+    (arrays of shape [i1 - i0, No] whose columns outside [j0, j1) are zero): the same call as
+    gemm() without materializing the whole output."""
+    Mo, No = out_shape(op, A, B)
+    i0, i1, j0, j1 = window
+    assert 0 <= i0 <= i1 <= Mo and 0 <= j0 <= j1 <= No
+    c = np.zeros((i1 - i0, No), np.float32)
+    cb = np.zeros((i1 - i0, No), np.uint16) if want_bf16 else None
+    oa, ob = A.operand(True), B.operand(False)
+    # the C routine addresses element (i, j) at base + i*No + j: hand it the base that puts
+    # row i0 at the start of the window buffer
+    rc = lib().fqo_gemm(op, C.byref(oa), C.byref(ob), A.g, i0, i1, j0, j1,
+                        C.c_void_p(c.ctypes.data - i0 * No * 4),
+                        C.c_void_p(cb.ctypes.data - i0 * No * 2) if cb is not None else None)
+    if rc != 0:
+        raise RuntimeError(f"fqo_gemm failed: {rc}")
+    return (c, cb) if want_bf16 else c
+
+
 def gemm_partials(op, A: QTensor, B: QTensor, kb: int, residual_term: bool, window=None):
     Mo, No = out_shape(op, A, B)
     i0, i1, j0, j1 = window if window is not None else (0, Mo, 0, No)

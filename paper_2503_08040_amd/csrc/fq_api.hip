@@ -4,6 +4,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "fq_device.h"
 #include "fq_kernels.h"
 
@@ -28,7 +30,7 @@ bool compute_layout(int32_t rows, int32_t cols, int32_t block, int32_t capacity,
   L->codes_t = want_t ? take((size_t)nb * FQ_BLOCK_BYTES) : (size_t)-1;
   L->scales = take((size_t)nb * 4);
   L->mask = take((size_t)nb);
-  L->fb_counters = take(8);
+  L->fb_counters = take(12);
   L->fb_list = take((size_t)capacity * 4);
   L->fb_slot = take((size_t)nb * 4);
   L->res_codes = take((size_t)capacity * FQ_BLOCK_BYTES);
@@ -163,19 +165,22 @@ fq_status quantize_impl(const void* x_bf16, int32_t rows, int32_t cols, int64_t 
   p.scales = out->scales; p.mask = out->mask;
   // Two alternating counters: this call counts in one and clears the other for the next call.
   // Under stream capture the launches are replayed without passing through here again, so the
-  // recorded form must not depend on which counter is clean: it clears both first and counts in
-  // counter 0, and the tensor is marked as fresh for the next call that is not captured.
+  // recorded form must not depend on which counter is clean: it clears all counters first and
+  // counts in counter 0.  A replay leaves counter 0 non-zero at a time the host cannot know, so
+  // from then on (epoch -1) every call into the tensor, captured or not, takes that form.
   hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
   const bool capturing =
       hipStreamIsCapturing(static_cast<hipStream_t>(hip_stream), &capture) == hipSuccess &&
       capture == hipStreamCaptureStatusActive;
-  const bool first = out->epoch == 0 || capturing;
-  const int live = capturing ? 0 : (out->epoch & 1);
+  const bool sticky = capturing || out->epoch < 0;
+  const bool first = out->epoch == 0 || sticky;
+  const int live = sticky ? 0 : (out->epoch & 1);
   p.fb_count = out->fb_counters + live;
   p.fb_count_next = out->fb_counters + (live ^ 1);
+  p.arrivals = out->fb_counters + 2;
   p.clear_both = (first || empty) ? 1 : 0;
   out->fb_count = empty ? out->fb_counters : p.fb_count;
-  if (capturing) out->epoch = 0;
+  if (sticky) out->epoch = -1;
   else out->epoch = empty ? 2 : (out->epoch >= (1 << 30) ? 2 + (live ^ 1) : out->epoch + 1);
   p.fb_list = out->fb_list; p.fb_slot = out->fb_slot;
   p.res_codes = out->res_codes; p.res_codes_t = out->res_codes_t; p.res_scales = out->res_scales;

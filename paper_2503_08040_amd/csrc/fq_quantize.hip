@@ -183,6 +183,52 @@ __device__ __forceinline__ float thread_absmax(const v4i (&raw)[4][2]) {
   return m;
 }
 
+// The ascending list of flagged block ids (the compaction step of the quantizer), written by
+// the workgroup that finishes its block last: by then every block's flag is in `mask`.  Flags
+// are read with device-scope loads (other workgroups wrote them, possibly through another L2).
+// The list holds the first `capacity` flagged ids when more blocks are flagged than that.
+__device__ inline void write_fb_list(const uint8_t* mask, int nb, int capacity, int32_t* fb_list,
+                                     int* wave_sum /* LDS, 4 ints */, int* base_sh /* LDS, 1 int */) {
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  if (t == 0) *base_sh = 0;
+  const uint32_t* m32 = reinterpret_cast<const uint32_t*>(mask);
+  const bool words_ok = (reinterpret_cast<uintptr_t>(mask) & 3) == 0;
+  for (int first = 0; first < nb; first += 4 * kThreads) {
+    // four consecutive flags per thread
+    const int b0 = first + 4 * t;
+    uint32_t f = 0;
+    if (b0 + 4 <= nb && words_ok) {
+      f = __hip_atomic_load(m32 + (b0 >> 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      for (int i = 0; i < 4; ++i)
+        if (b0 + i < nb)
+          f |= (uint32_t)__hip_atomic_load(mask + b0 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+               << (8 * i);
+    }
+    f &= 0x01010101u;
+    const int mine = (int)((f * 0x01010101u) >> 24);
+    // exclusive prefix over the workgroup
+    int incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int v = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += v;
+    }
+    __syncthreads();   // base_sh / wave_sum of the previous trip have been read
+    if (lane == 63) wave_sum[w] = incl;
+    __syncthreads();
+    int pos = *base_sh + incl - mine;
+    for (int j = 0; j < w; ++j) pos += wave_sum[j];
+    for (int i = 0; i < 4; ++i)
+      if ((f >> (8 * i)) & 1u) {
+        if (pos < capacity) fb_list[pos] = b0 + i;
+        ++pos;
+      }
+    __syncthreads();
+    if (t == 0) *base_sh += wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+  }
+}
+
 }  // namespace
 
 // kErr: the fallback decision uses a block quantization-error metric (criteria 3, 4), which
@@ -195,7 +241,8 @@ __global__ __launch_bounds__(kThreads, kErr ? 2 : 4)
 void quantize_kernel(QuantParams p) {
   __shared__ float red[4];
   __shared__ double redd[kErr ? 8 : 1];
-  __shared__ int slot_sh;
+  __shared__ int slot_sh, last_sh, scan_base_sh;
+  __shared__ int scan_sh[4];
   __shared__ __attribute__((aligned(16))) int8_t img[kWantT ? kBlockBytes : 16];
 
   const int blk = blockIdx.x;
@@ -204,39 +251,11 @@ void quantize_kernel(QuantParams p) {
   const int cc = t & 7, rp = t >> 3;
   const int row0 = bi * kBlock, col0 = bk * kBlock + cc * 16;
 
-  // ---- load 4 x 16 bf16, zero outside the matrix
   v4i raw[4][2];
-  const bool inner = (row0 + kBlock <= p.rows) && (bk * kBlock + kBlock <= p.cols) && p.vec_ok;
-  if (inner) {
-#pragma unroll
-    for (int pz = 0; pz < 4; ++pz) {
-      const uint16_t* src = p.x + (int64_t)(row0 + pz * 32 + rp) * p.ld + col0;
-      raw[pz][0] = *reinterpret_cast<const v4i*>(src);
-      raw[pz][1] = *reinterpret_cast<const v4i*>(src + 8);
-    }
-  } else {
-#pragma unroll
-    for (int pz = 0; pz < 4; ++pz) {
-      const int r = row0 + pz * 32 + rp;
-#pragma unroll
-      for (int d = 0; d < 8; ++d) {
-        uint32_t w = 0;
-#pragma unroll
-        for (int hh = 0; hh < 2; ++hh) {
-          const int c = col0 + 2 * d + hh;
-          if (r < p.rows && c < p.cols) w |= (uint32_t)p.x[(int64_t)r * p.ld + c] << (16 * hh);
-        }
-        raw[pz][d >> 2][d & 3] = (int)w;
-      }
-    }
-  }
+  load_block(p, bi, bk, rp, cc, raw);
 
   // ---- step 1: a = max|G| / 127, codes = round(G / a)           (Sec. 3.1)
-  float m = 0.0f;
-#pragma unroll
-  for (int pz = 0; pz < 4; ++pz)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) m = fmaxf(m, fabsf(x_at(raw, pz, e)));
+  const float m = thread_absmax(raw);
   const float amax = block_max(m, red);
   const float a = __fdiv_rn(amax, 127.0f);
   const float a_rcp = fast_recip(a);
@@ -328,18 +347,24 @@ void quantize_kernel(QuantParams p) {
     if (u && t == 0) slot_early = atomicAdd(p.fb_count, 1);
   }
 
-  int slot = -1;
-  if (u) {
-    if (t == 0) slot_sh = (slot_early < p.capacity) ? slot_early : -2;
-    __syncthreads();
-    slot = slot_sh;
-  }
+  // ---- per-block outputs; the last workgroup to get here compacts the list of flagged blocks
   if (t == 0) {
+    const int slot0 = u ? ((slot_early < p.capacity) ? slot_early : -2) : -1;
     p.scales[blk] = a;
-    p.mask[blk] = u ? 1 : 0;
-    p.fb_slot[blk] = slot;
-    if (slot >= 0) p.fb_list[slot] = blk;
+    p.fb_slot[blk] = slot0;
     if (blk == 0) *p.fb_count_next = 0;   // ready for the next call into this tensor
+    __hip_atomic_store(p.mask + blk, (uint8_t)(u ? 1 : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __threadfence();
+    const int arrived = atomicAdd(p.arrivals, 1);
+    slot_sh = slot0;
+    last_sh = arrived == (int)gridDim.x - 1;
+  }
+  __syncthreads();
+  const int slot = slot_sh;
+  if (last_sh) {      // uniform over the workgroup
+    __threadfence();
+    write_fb_list(p.mask, (int)gridDim.x, p.capacity, p.fb_list, scan_sh, &scan_base_sh);
+    if (t == 0) *p.arrivals = 0;          // ready for the next call
   }
   if (slot < 0) return;  // uniform over the workgroup
 
@@ -468,10 +493,11 @@ __global__ void fill_mask_kernel(uint8_t* mask, int nb, int v) {
 }
 
 // Clears both slot counters: first use of a tensor, or an empty input.
-__global__ void clear_counters_kernel(int32_t* live, int32_t* next) {
+__global__ void clear_counters_kernel(int32_t* live, int32_t* next, int32_t* arrivals) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     *live = 0;
     *next = 0;
+    *arrivals = 0;
   }
 }
 
@@ -486,7 +512,8 @@ __global__ void untile_kernel(const int8_t* tiled, int rows, int cols, int nbc, 
 
 hipError_t launch_quantize(const QuantParams& p, hipStream_t st) {
   if (p.clear_both)
-    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, st, p.fb_count, p.fb_count_next);
+    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, st, p.fb_count, p.fb_count_next,
+                       p.arrivals);
   const int nb = p.nbr * p.nbc;
   if (nb > 0 && p.crit == 5) {
     if (p.topk <= 0 || p.topk >= nb) {

@@ -62,3 +62,25 @@ def test_step_replays_from_a_graph():
         assert int(qx.view("fb_count").cpu()[0]) == n_ref
         counts.append(n_ref)
     assert len(set(counts)) > 1          # the replays really saw different inputs
+
+    # eager calls into the captured tensor between replays: counts and slots stay right
+    for rep in range(3):
+        for j in range(rep + 1):         # one, two, three eager calls in a row
+            x_new = _inputs(20 + 3 * rep + j, (M, K))
+            q_ref = fq.fq_quantize(x_new, fq.FQ_CRIT_ABSMAX_GT, 8.0)
+            n_ref = fq.fq_qtensor_check(q_ref)
+            gu.announce(f"eager call {j} into the captured tensor after replay round {rep}")
+            fq.fq_quantize(x_new, fq.FQ_CRIT_ABSMAX_GT, 8.0, out=qx)
+            assert fq.fq_qtensor_check(qx) == n_ref
+            slot = qx.view("fb_slot").cpu().numpy()
+            assert sorted(slot[slot >= 0].tolist()) == list(range(n_ref))
+            assert torch.equal(qx.view("fb_list")[:n_ref], q_ref.view("fb_list")[:n_ref])
+            assert torch.equal(fq.fq_gemm(fq.FQ_OP_NT, qx, qw), fq.fq_gemm(fq.FQ_OP_NT, q_ref, qw))
+        x_new = _inputs(40 + rep, (M, K))
+        q_ref = fq.fq_quantize(x_new, fq.FQ_CRIT_ABSMAX_GT, 8.0)
+        y_ref = fq.fq_gemm(fq.FQ_OP_NT, q_ref, qw)
+        x_static.copy_(x_new)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_ref), f"replay after eager calls, round {rep}"
+        assert int(qx.view("fb_count").cpu()[0]) == fq.fq_qtensor_check(q_ref)

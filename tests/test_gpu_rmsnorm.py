@@ -82,6 +82,11 @@ def test_rmsnorm_forward_backward(shape, parts):
     _close(_bits(dx), odx, floor, "dx", min_exact=0.98)
     mag = (np.abs(_f(bdy)) * xh).sum(axis=0)
     assert np.all(np.abs(dw.cpu().numpy().astype(np.float64) - odw) <= 1e-5 * mag + 1e-30), "dw"
+    # end to end: the oracle's backward on the oracle's own forward outputs (its rstd, not the
+    # GPU's).  The two rstd agree to 2e-6, which the floor of the bracket is widened by.
+    odx2, odw2 = fqo.rmsnorm_backward(bdy, octx, orstd, bw)
+    _close(_bits(dx), odx2, 4.0 * floor, "dx (oracle rstd)", min_exact=0.98)
+    assert np.all(np.abs(dw.cpu().numpy().astype(np.float64) - odw2) <= 1.2e-5 * mag + 1e-30), "dw (oracle rstd)"
 
 
 def test_rmsnorm_strides_determinism_and_errors():

@@ -342,3 +342,20 @@ def test_bf16_output_ties_round_to_even():
     c, cb = fqo.gemm(fqo.OP_NT, qa, qb, want_bf16=True)
     assert c[0, 0] == 257 and c[1, 0] == 259
     assert cb[0, 0] == 0x4380 and synth.bf16_bits_to_f32(cb)[1, 0] == 260
+
+
+def test_gemm_window_returns_the_same_values_as_the_full_call():
+    """fqo.gemm_window (only the window's rows are materialized) against fqo.gemm."""
+    rng = np.random.default_rng(11)
+    a = synth.to_bf16_bits(rng.standard_normal((70, 40)).astype(np.float32))
+    b = synth.to_bf16_bits(rng.standard_normal((50, 40)).astype(np.float32))
+    qa = fqo.quantize(a, 16, fqo.CRIT_ABSMAX_GT, 2.5)
+    qb = fqo.quantize(b, 16, fqo.CRIT_NONE, 0.0)
+    full, fullb = fqo.gemm(fqo.OP_NT, qa, qb, want_bf16=True)
+    for win in ((0, 70, 0, 50), (16, 48, 5, 37), (69, 70, 49, 50), (10, 10, 0, 50)):
+        i0, i1, j0, j1 = win
+        w32, wb = fqo.gemm_window(fqo.OP_NT, qa, qb, win, want_bf16=True)
+        assert w32.shape == (i1 - i0, 50)
+        assert np.array_equal(w32[:, j0:j1], full[i0:i1, j0:j1])
+        assert np.array_equal(wb[:, j0:j1], fullb[i0:i1, j0:j1])
+        assert not w32[:, :j0].any() and not w32[:, j1:].any()
