@@ -73,7 +73,9 @@ typedef enum {
   FQ_ERR_BLOCK = -3,    /* block size other than 128                           */
   FQ_ERR_ENUM = -4,     /* unknown enum value, or B operand quantized with fallback */
   FQ_ERR_CAPACITY = -5, /* more flagged blocks than `capacity` (fq_qtensor_check) */
-  FQ_ERR_HIP = -6       /* a HIP call failed                                   */
+  FQ_ERR_HIP = -6,      /* a HIP call failed                                   */
+  FQ_ERR_SCRATCH = -7   /* fq_rmsnorm_backward_static: the call needs more scratch
+                           memory than the library's built-in buffer holds         */
 } fq_status;
 
 /* Fallback criterion.  NONE: u = 0 everywhere (plain block INT8, Eq. (1)).
@@ -305,6 +307,25 @@ fq_status fq_rmsnorm_backward(const void *dy_bf16, int64_t ld_dy, const uint8_t 
                               const float *ctx_scales, const float *rstd, const void *w_bf16,
                               int32_t rows, int32_t cols, void *dx_bf16, int64_t ldo, float *dw,
                               float *workspace, int32_t n_parts, void *hip_stream);
+
+/*
+ * fq_rmsnorm_backward for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and the
+ * same results, bit for bit, but the workspace is a buffer of FQ_STATIC_SCRATCH_FLOATS floats
+ * (16 MiB) built into the library, one copy per GPU, held until the process ends.  The call
+ * allocates and frees nothing.  FQ_ERR_SCRATCH if n_parts * cols + rows exceeds
+ * FQ_STATIC_SCRATCH_FLOATS (choose a smaller n_parts); other arguments and errors as
+ * fq_rmsnorm_backward.  All calls on one GPU share that GPU's buffer: calls that may overlap
+ * in time on one GPU (different streams or threads) race on it and must be ordered by the
+ * caller.  Nothing in the buffer needs clearing between calls (every element a call reads
+ * was written by that call).
+ */
+#define FQ_STATIC_SCRATCH_FLOATS (4 * 1024 * 1024)
+fq_status fq_rmsnorm_backward_static(const void *dy_bf16, int64_t ld_dy,
+                                     const uint8_t *ctx_packed, const float *ctx_scales,
+                                     const float *rstd, const void *w_bf16, int32_t rows,
+                                     int32_t cols, void *dx_bf16, int64_t ldo, float *dw,
+                                     int32_t n_parts, void *hip_stream);
 
 /*
  * Fallback block GEMM (Alg. 1).  For every output tile, k-blocks ascending:

@@ -13,8 +13,9 @@ FQ_BLOCK_BYTES = 16384
 FQ_CTX_GROUP = 128
 FQ_CTX_GROUP_BYTES = 160
 
-FQ_OK, FQ_ERR_NULL, FQ_ERR_SHAPE, FQ_ERR_BLOCK, FQ_ERR_ENUM, FQ_ERR_CAPACITY, FQ_ERR_HIP = \
-    0, -1, -2, -3, -4, -5, -6
+FQ_OK, FQ_ERR_NULL, FQ_ERR_SHAPE, FQ_ERR_BLOCK, FQ_ERR_ENUM, FQ_ERR_CAPACITY, FQ_ERR_HIP, \
+    FQ_ERR_SCRATCH = 0, -1, -2, -3, -4, -5, -6, -7
+FQ_STATIC_SCRATCH_FLOATS = 4 * 1024 * 1024
 FQ_CRIT_NONE, FQ_CRIT_ABSMAX_GT, FQ_CRIT_ALL, FQ_CRIT_L1_GT, FQ_CRIT_L1REL_GT, FQ_CRIT_TOPK = \
     0, 1, 2, 3, 4, 5
 FQ_OP_NT, FQ_OP_NN, FQ_OP_TN = 0, 1, 2
@@ -28,7 +29,7 @@ EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr
            "fq_gemm_debug_partials", "fq_codes_to_rowmajor", "fq_qtensor_check",
            "fq_status_string", "fq_ctx_packed_bytes", "fq_ctx_scales_bytes", "fq_ctx_quantize",
            "fq_ctx_dequantize", "fq_gemm_tile_plan", "fq_glu_forward", "fq_glu_backward", "fq_rmsnorm_forward",
-           "fq_rmsnorm_backward"]
+           "fq_rmsnorm_backward", "fq_rmsnorm_backward_static"]
 
 
 class fq_qtensor(C.Structure):
@@ -112,6 +113,10 @@ def lib():
         L.fq_rmsnorm_backward.argtypes = [C.c_void_p, C.c_int64] + [C.c_void_p] * 4 + \
                                          [C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
                                           C.c_void_p, C.c_int32, C.c_void_p]
+        L.fq_rmsnorm_backward_static.restype = C.c_int
+        L.fq_rmsnorm_backward_static.argtypes = [C.c_void_p, C.c_int64] + [C.c_void_p] * 4 + \
+                                                [C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
+                                                 C.c_void_p, C.c_int32, C.c_void_p]
         L.fq_gemm_tile_plan.restype = C.c_int
         L.fq_gemm_tile_plan.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32)]
         _lib = L
@@ -400,6 +405,19 @@ def fq_rmsnorm_forward(x, w, eps, stream=None):
                                     C.c_void_p(rstd.data_ptr()), _stream_ptr(stream)),
            "fq_rmsnorm_forward")
     return y, rstd, (packed, scales)
+
+
+def fq_rmsnorm_backward_static(dy, ctx, rstd, w, dx, dw, n_parts=64, stream=None):
+    """fq_rmsnorm_backward into caller-provided dx (bf16 [rows, cols]) and dw (float32 [cols])
+    with the library's built-in scratch buffer: the call allocates nothing."""
+    rows, cols = dy.shape
+    _check(lib().fq_rmsnorm_backward_static(C.c_void_p(dy.data_ptr()), _pitch(dy),
+                                            C.c_void_p(ctx[0].data_ptr()), C.c_void_p(ctx[1].data_ptr()),
+                                            C.c_void_p(rstd.data_ptr()), C.c_void_p(w.data_ptr()),
+                                            rows, cols, C.c_void_p(dx.data_ptr()), _pitch(dx),
+                                            C.c_void_p(dw.data_ptr()), int(n_parts), _stream_ptr(stream)),
+           "fq_rmsnorm_backward_static")
+    return dx, dw
 
 
 def fq_rmsnorm_backward(dy, ctx, rstd, w, n_parts=256, stream=None):

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 
 #include "fq_device.h"
 #include "fq_kernels.h"
@@ -366,6 +367,42 @@ fq_status fq_rmsnorm_backward(const void* dy_bf16, int64_t ld_dy, const uint8_t*
   return FQ_OK;
 }
 
+// Scratch memory of fq_rmsnorm_backward_static: the partial column sums and row means that
+// fq_rmsnorm_backward takes through its workspace argument.  Host code never uses the array's
+// name as an address: each device's copy is looked up once with hipGetSymbolAddress.
+static __device__ __align__(256) float scratch[FQ_STATIC_SCRATCH_FLOATS];
+
+namespace {
+constexpr int kScratchDevices = 64;
+float* g_scratch_ptr[kScratchDevices];          // per device, nullptr until looked up
+std::mutex g_scratch_mutex;
+
+// The current device's copy of `scratch`, or nullptr if the lookup fails.
+float* scratch_of_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kScratchDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = static_cast<float*>(ptr);
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+fq_status fq_rmsnorm_backward_static(const void* dy_bf16, int64_t ld_dy, const uint8_t* ctx_packed,
+                                     const float* ctx_scales, const float* rstd, const void* w_bf16,
+                                     int32_t rows, int32_t cols, void* dx_bf16, int64_t ldo,
+                                     float* dw, int32_t n_parts, void* hip_stream) {
+  if (rows < 0 || cols < 1 || n_parts < 1 || n_parts > 65535) return FQ_ERR_SHAPE;
+  if ((int64_t)n_parts * cols + rows > (int64_t)FQ_STATIC_SCRATCH_FLOATS) return FQ_ERR_SCRATCH;
+  float* ws = scratch_of_current_device();
+  if (!ws) return FQ_ERR_HIP;
+  return fq_rmsnorm_backward(dy_bf16, ld_dy, ctx_packed, ctx_scales, rstd, w_bf16, rows, cols,
+                             dx_bf16, ldo, dw, ws, n_parts, hip_stream);
+}
+
 fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,
                   int64_t ldc, void* hip_stream) {
   fq::GemmParams g;
@@ -443,6 +480,7 @@ const char* fq_status_string(fq_status s) {
     case FQ_ERR_ENUM: return "invalid enum value or B operand quantized with fallback";
     case FQ_ERR_CAPACITY: return "more flagged blocks than residual slots";
     case FQ_ERR_HIP: return "HIP call failed";
+    case FQ_ERR_SCRATCH: return "needs more scratch memory than the library's built-in buffer holds";
   }
   return "unknown status";
 }

@@ -109,7 +109,7 @@ def test_gemm_rejects_bad_arguments_on_the_host():
 
 
 def test_status_strings():
-    for s in range(0, -7, -1):
+    for s in range(0, -8, -1):
         assert fq.status_string(s) and "unknown" not in fq.status_string(s)
     assert "unknown" in fq.status_string(-99)
 
