@@ -22,9 +22,28 @@ sys.path.insert(0, ROOT)
 
 INT8_PEAK_TOPS = 5000.0     # MI355X dense INT8 MFMA peak (published), TOP/s
 HBM_PEAK_GBS = 8000.0
-# HBM-side bytes per fq_gemm launch from rocprofv3 FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00), both
-# scaled by what the same counters read for a 1 GiB copy (profiles/gemm_quantize_cfg2_hbm_traffic.md)
-MEASURED_GEMM_TRAFFIC_BYTES = {"cfg2_glu_upgate_4096x4096x11008": 291.9e6 + 90.2e6}
+GEMM_SOURCE = os.path.join(ROOT, "paper_2503_08040_amd", "csrc", "fq_gemm.hip")
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gemm_quantize_cfg2_hbm_traffic.md")
+
+
+def measured_gemm_traffic(workload_name):
+    """HBM-side bytes per fq_gemm launch as measured with rocprofv3 (FETCH_SIZE, WRITE_SIZE,
+    each scaled by what the same counter reads for a copy of known size): read from the
+    committed profile summary, which records the workload and the SHA-256 of the kernel source
+    it was measured on.  None when the kernel source has changed since (the figure would be
+    stale) or the summary does not cover this workload."""
+    import hashlib
+    import re
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+        sha = hashlib.sha256(open(GEMM_SOURCE, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    m = re.search(r"^gemm_traffic: workload=(\S+) bytes_per_launch=(\d+) fq_gemm_hip_sha256=([0-9a-f]{64})\s*$",
+                  text, flags=re.M)
+    if not m or m.group(1) != workload_name or m.group(3) != sha:
+        return None
+    return int(m.group(2))
 
 
 def log(*a):
@@ -208,6 +227,68 @@ def sweep(args):
             "crossover_fraction_random": None if cross is None else round(cross, 3)}
 
 
+def overhead_curve(seconds_per_point=0.4, iters=30):
+    """The square problem of workload config 5 (M = K = N = 8192) at a few fallback fractions:
+    GEMM time and overhead against f = 0, quantize time, and the fraction at which quantize +
+    fallback GEMM stops being faster than the bf16 GEMM (Sec. 6.3, App. B), interpolated
+    linearly between the measured points.  Inputs follow config 5's recipe but are drawn on the
+    device (N(0,1); exactly round(f * 4096) blocks get one column x100; "random": blocks drawn
+    uniformly, "sequential": packed into the fewest block-rows; theta = 10), so that the default
+    run stays short; bench.py --sweep runs the full table on the host-generated inputs."""
+    import torch
+    import paper_2503_08040_amd as fq
+    M = K = N = 8192
+    nbr = nbc = M // 128
+    ops = 2.0 * M * N * K
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5)
+    base = torch.randn((M, K), device="cuda", generator=g, dtype=torch.float32).to(torch.bfloat16)
+    w = torch.randn((N, K), device="cuda", generator=g, dtype=torch.float32).to(torch.bfloat16)
+    y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    qx = fq.QTensor(M, K)
+    qw = fq.fq_quantize(w, fq.FQ_CRIT_NONE, 0.0, capacity=0)
+    ms_bf16 = _time_loop(lambda: torch.matmul(base, w.t(), out=y), seconds_per_point, iters)
+    points = []
+    for placement, frac in (("random", 0.0), ("random", 0.05), ("random", 0.2), ("sequential", 0.05)):
+        n_fb = int(round(frac * nbr * nbc))
+        ids = (torch.randperm(nbr * nbc, device="cuda", generator=g)[:n_fb] if placement == "random"
+               else torch.arange(n_fb, device="cuda"))
+        x = base.clone()
+        if n_fb:
+            bi, bk = ids // nbc, ids % nbc
+            col = bk * 128 + torch.randint(0, 128, (n_fb,), device="cuda", generator=g)
+            rows = (bi[:, None] * 128 + torch.arange(128, device="cuda")[None, :]).reshape(-1)
+            cols = col[:, None].expand(n_fb, 128).reshape(-1)
+            x[rows, cols] = (x[rows, cols].float() * 100.0).to(torch.bfloat16)
+        fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, 10.0, out=qx)
+        got = fq.fq_qtensor_check(qx)
+        ms_q = _time_loop(lambda: fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, 10.0, out=qx), 0.1, iters)
+        ms_g = _time_loop(lambda: fq.fq_gemm(fq.FQ_OP_NT, qx, qw, out=y), seconds_per_point, iters)
+        points.append({"placement": placement, "f": round(got / (nbr * nbc), 4),
+                       "ms_quantize": round(ms_q, 4), "ms_gemm": round(ms_g, 4),
+                       "tops_quant_plus_gemm": round(ops / (ms_q + ms_g) / 1e9, 1)})
+        del x
+    t0 = points[0]["ms_gemm"]
+    for pt in points:
+        pt["gemm_overhead_vs_f0"] = round(pt["ms_gemm"] / t0, 3)
+        pt["speedup_vs_bf16"] = round(ms_bf16 / (pt["ms_quantize"] + pt["ms_gemm"]), 3)
+    rnd = [pt for pt in points if pt["placement"] == "random"]
+    total = lambda pt: pt["ms_quantize"] + pt["ms_gemm"]
+    if total(rnd[0]) > ms_bf16:
+        cross = 0.0                      # slower than bf16 even without fallback
+    else:
+        cross = None                     # faster than bf16 at every measured fraction
+        for a, b in zip(rnd, rnd[1:]):
+            if total(a) <= ms_bf16 < total(b):
+                cross = a["f"] + (b["f"] - a["f"]) * (ms_bf16 - total(a)) / (total(b) - total(a))
+    return {"workload": "cfg5_square_8192 (device-drawn inputs)", "bf16_gemm_ms": round(ms_bf16, 4),
+            "bf16_tflops": round(ops / ms_bf16 / 1e9, 1), "points": points,
+            "crossover_fraction_random": None if cross is None else round(cross, 3),
+            "crossover_note": "largest fallback fraction (random placement) at which quantize + "
+                              "fallback GEMM is still as fast as the bf16 GEMM, linear between the "
+                              "measured points; null: beyond the last measured fraction"}
+
+
 def backward(args):
     """Sec. 5.1 / 5.3: dY is block-quantized with stochastic rounding, then two plain block GEMMs
     dX = dY W and dW = dY^T X_ctx (X_ctx: the stochastic block-INT8 context stored in forward)."""
@@ -326,6 +407,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="config-5 sweep (8192^3): fallback fraction x placement, overhead curve and "
                          "crossover against the bf16 GEMM; prints one JSON object with a table")
+    ap.add_argument("--no-overhead-curve", action="store_true",
+                    help="skip the compact config-5 overhead curve (about 10 s)")
     ap.add_argument("--no-mfma-ceiling", action="store_true",
                     help="skip the register-only MFMA throughput probe (about 3 s)")
     ap.add_argument("--backward", action="store_true",
@@ -448,9 +531,9 @@ def main():
         "gemm_only_tops": round(ops / (ms_gemm * 1e-3) / 1e12, 2),
         "quantizer_gbs": round(quant_bytes / (ms_quant * 1e-3) / 1e9, 1),
         "roofline": {"bound": "mfma", "kernel": "fq::gemm_kernel",
-                     "achieved": round(achieved, 2), "peak": INT8_PEAK_TOPS, "unit": "TFLOP/s",
+                     "achieved": round(achieved, 2), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
                      "frac": round(achieved / INT8_PEAK_TOPS, 4),
-                     "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(wl.name)
+                     "traffic": measured_gemm_traffic(wl.name)
                      if args.out_dtype == "bf16" else None,
                      "note": "INT8 ops: 2*M*N*K*(1+f) per launch / HIP-event time of fq_gemm, from "
                              "an instrumented repeat of the K timed steps (ms_per_step_instrumented)"},
@@ -496,6 +579,9 @@ def main():
             r = subprocess.run([tool], capture_output=True, text=True, timeout=120)
             if r.returncode == 0:
                 result["mfma_ceiling"] = json.loads(r.stdout.strip().splitlines()[-1])
+    if not args.no_overhead_curve:
+        log("[bench] config-5 overhead curve")
+        result["overhead_curve_cfg5"] = overhead_curve()
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a bounded sample")
         result["cpu_baseline"], window, oracle_out = cpu_baseline(wl)

@@ -127,10 +127,12 @@ typedef struct {
   int32_t *fb_count;     /* [1]  number of flagged blocks (may exceed capacity).
                             Points at one of the two fb_counters; fq_quantize
                             re-points it on every call                           */
-  int32_t *fb_counters;  /* [3]  library-managed: two alternating slot counters (a call
-                            counts in one and clears the other for the next call, so the
-                            quantizer is a single kernel launch) and a counter of the
-                            workgroups that have finished their block               */
+  int32_t *fb_counters;  /* [4 + 2*ceil(nbr*nbc/32)], 8-byte aligned, library-managed:
+                            two alternating slot counters (a call counts in one and
+                            clears the other for the next call, so the quantizer is a
+                            single kernel launch), a counter of completed groups of 32
+                            blocks, one unused word, and one 64-bit word of decision
+                            bits per group (from which fb_list is written)            */
   int32_t *fb_list;      /* [capacity] ascending list of the flagged blocks' ids bi*nbc+bk
                             (the first min(fb_count, capacity) entries are valid; when more
                             blocks are flagged than `capacity`, the lowest `capacity` ids);
@@ -165,7 +167,7 @@ fq_status fq_qtensor_bind(void *base, int32_t rows, int32_t cols, int32_t block,
  * Outputs: every buffer of `out` that is not NULL-optional (codes, scales,
  * mask, fb_count, fb_list, fb_slot; res_* when capacity > 0; *_t when set).
  * The first call into a freshly bound tensor also clears fb_counters.
- * fb_list is written by the workgroup that finishes last, from the flags of all blocks.
+ * fb_list is written by the workgroup that records the last decision, from all blocks' flags.
  * out->capacity may be 0 only with FQ_CRIT_NONE.  If more blocks are flagged
  * than there are slots, the surplus blocks get fb_slot = -2, fb_count still
  * reports the true count, and any fq_gemm using the tensor as A writes NaN to

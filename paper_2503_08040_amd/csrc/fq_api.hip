@@ -31,7 +31,7 @@ bool compute_layout(int32_t rows, int32_t cols, int32_t block, int32_t capacity,
   L->codes_t = want_t ? take((size_t)nb * FQ_BLOCK_BYTES) : (size_t)-1;
   L->scales = take((size_t)nb * 4);
   L->mask = take((size_t)nb);
-  L->fb_counters = take(12);
+  L->fb_counters = take(16 + 8 * (size_t)((nb + 31) / 32));
   L->fb_list = take((size_t)capacity * 4);
   L->fb_slot = take((size_t)nb * 4);
   L->res_codes = take((size_t)capacity * FQ_BLOCK_BYTES);
@@ -178,7 +178,8 @@ fq_status quantize_impl(const void* x_bf16, int32_t rows, int32_t cols, int64_t 
   const int live = sticky ? 0 : (out->epoch & 1);
   p.fb_count = out->fb_counters + live;
   p.fb_count_next = out->fb_counters + (live ^ 1);
-  p.arrivals = out->fb_counters + 2;
+  p.fb_groups_done = out->fb_counters + 2;
+  p.fb_words = reinterpret_cast<unsigned long long*>(out->fb_counters + 4);
   p.clear_both = (first || empty) ? 1 : 0;
   out->fb_count = empty ? out->fb_counters : p.fb_count;
   if (sticky) out->epoch = -1;

@@ -23,7 +23,8 @@ struct QuantParams {
   uint8_t* mask;
   int32_t* fb_count;       // live slot counter of this call (zero on entry)
   int32_t* fb_count_next;  // counter of the next call: cleared by this call
-  int32_t* arrivals;       // workgroups that have written their block's flag (zero between calls)
+  int32_t* fb_groups_done;       // groups of 32 blocks whose decisions are all recorded (zero between calls)
+  unsigned long long* fb_words;  // per group: decided bits | flagged bits << 32 (zero between calls)
   int clear_both;          // first use of the tensor (or empty input): clear all counters first
   int32_t* fb_list;
   int32_t* fb_slot;

@@ -183,32 +183,35 @@ __device__ __forceinline__ float thread_absmax(const v4i (&raw)[4][2]) {
   return m;
 }
 
-// The ascending list of flagged block ids (the compaction step of the quantizer), written by
-// the workgroup that finishes its block last: by then every block's flag is in `mask`.  Flags
-// are read with device-scope loads (other workgroups wrote them, possibly through another L2).
-// The list holds the first `capacity` flagged ids when more blocks are flagged than that.
-__device__ inline void write_fb_list(const uint8_t* mask, int nb, int capacity, int32_t* fb_list,
-                                     int* wave_sum /* LDS, 4 ints */, int* base_sh /* LDS, 1 int */) {
+// The bits block b contributes to its group's word: "decided" and, if u, "flagged".
+__device__ inline unsigned long long my_bits(int b, bool u) {
+  return (1ull << (b & 31)) | ((u ? 1ull : 0ull) << (32 + (b & 31)));
+}
+
+// The ascending list of flagged block ids (the compaction step of the quantizer).  Every
+// workgroup records its decision with one 64-bit atomic OR into the word of its group of 32
+// blocks (bit b % 32: "decided", bit 32 + b % 32: "flagged"), issued as soon as the decision is
+// known so that its round trip hides behind the quantization of the block.  The workgroup whose
+// OR completes a group counts the group; the one that counts the last group knows that every
+// word is final (each OR was performed before the count it led to) and writes the list from the
+// words, which it then clears for the next call.  No fence is needed: the words are only ever
+// touched by device-scope atomics.  The list holds the lowest `capacity` ids when more blocks
+// are flagged than that.
+__device__ inline void write_fb_list(unsigned long long* words, int nb, int capacity,
+                                     int32_t* fb_list, int* wave_sum /* LDS, 4 ints */,
+                                     int* base_sh /* LDS, 1 int */) {
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int n_words = (nb + 31) >> 5;
   if (t == 0) *base_sh = 0;
-  const uint32_t* m32 = reinterpret_cast<const uint32_t*>(mask);
-  const bool words_ok = (reinterpret_cast<uintptr_t>(mask) & 3) == 0;
-  for (int first = 0; first < nb; first += 4 * kThreads) {
-    // four consecutive flags per thread
-    const int b0 = first + 4 * t;
+  for (int first = 0; first < n_words; first += kThreads) {
+    const int wi = first + t;
     uint32_t f = 0;
-    if (b0 + 4 <= nb && words_ok) {
-      f = __hip_atomic_load(m32 + (b0 >> 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    } else {
-      for (int i = 0; i < 4; ++i)
-        if (b0 + i < nb)
-          f |= (uint32_t)__hip_atomic_load(mask + b0 + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-               << (8 * i);
+    if (wi < n_words) {
+      f = (uint32_t)(__hip_atomic_load(words + wi, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32);
+      __hip_atomic_store(words + wi, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    f &= 0x01010101u;
-    const int mine = (int)((f * 0x01010101u) >> 24);
-    // exclusive prefix over the workgroup
-    int incl = mine;
+    const int mine = __popc(f);
+    int incl = mine;      // inclusive prefix over the wavefront
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
       const int v = __shfl_up(incl, off, 64);
@@ -219,11 +222,12 @@ __device__ inline void write_fb_list(const uint8_t* mask, int nb, int capacity, 
     __syncthreads();
     int pos = *base_sh + incl - mine;
     for (int j = 0; j < w; ++j) pos += wave_sum[j];
-    for (int i = 0; i < 4; ++i)
-      if ((f >> (8 * i)) & 1u) {
-        if (pos < capacity) fb_list[pos] = b0 + i;
-        ++pos;
-      }
+    while (f) {
+      const int bit = __ffs(f) - 1;
+      f &= f - 1;
+      if (pos < capacity) fb_list[pos] = wi * 32 + bit;
+      ++pos;
+    }
     __syncthreads();
     if (t == 0) *base_sh += wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
   }
@@ -265,10 +269,14 @@ void quantize_kernel(QuantParams p) {
   // trip of the atomic is hidden behind the quantization of the block.          (Sec. 4.4)
   bool u = false;
   int slot_early = -1;
+  unsigned long long group_before = 0;   // thread 0: the group's word before this block's bits
   if (!kErr) {
     // criterion 5: the decision was taken by topk_select_kernel and is read from the mask
     u = p.crit == 2 || (p.crit == 1 && amax > p.theta) || (p.crit == 5 && p.mask[blk] != 0);
-    if (u && t == 0) slot_early = atomicAdd(p.fb_count, 1);
+    if (t == 0) {
+      if (u) slot_early = atomicAdd(p.fb_count, 1);
+      group_before = atomicOr(p.fb_words + (blk >> 5), my_bits(blk, u));
+    }
   }
 
   v4i q[4];
@@ -316,6 +324,36 @@ void quantize_kernel(QuantParams p) {
     }
   }
 
+  // ---- per-block outputs; the workgroup that completes the last group of 32 blocks writes
+  // the list of flagged blocks.  Runs before the block's codes are stored (the two atomics
+  // issued after the decision have had the whole quantization to come back, and no store is
+  // pending that the wait for them would have to sit out); with an error-based criterion
+  // the decision is only known after the codes, so it runs there.
+  int slot = -1;
+  auto record_block = [&]() {
+    if (t == 0) {
+      const int slot0 = u ? ((slot_early < p.capacity) ? slot_early : -2) : -1;
+      p.scales[blk] = a;
+      p.mask[blk] = u ? 1 : 0;
+      p.fb_slot[blk] = slot0;
+      if (blk == 0) *p.fb_count_next = 0;   // ready for the next call into this tensor
+      slot_sh = slot0;
+      const int nb = (int)gridDim.x, g = blk >> 5;
+      const uint32_t full = (nb - 32 * g >= 32) ? 0xFFFFFFFFu : ((1u << (nb - 32 * g)) - 1u);
+      const uint32_t decided = (uint32_t)group_before | (1u << (blk & 31));
+      bool last = false;
+      if (decided == full) last = atomicAdd(p.fb_groups_done, 1) == ((nb + 31) >> 5) - 1;
+      last_sh = last;
+    }
+    __syncthreads();
+    slot = slot_sh;
+    if (last_sh) {      // uniform over the workgroup
+      write_fb_list(p.fb_words, (int)gridDim.x, p.capacity, p.fb_list, scan_sh, &scan_base_sh);
+      if (t == 0) *p.fb_groups_done = 0;    // ready for the next call
+    }
+  };
+  if (!kErr) record_block();
+
   forget_unpacked(raw);
   int8_t* cdst = p.codes + (int64_t)blk * kBlockBytes;
 #pragma unroll
@@ -344,28 +382,13 @@ void quantize_kernel(QuantParams p) {
     block_sum2(l1, l1x, redd);
     if (p.crit == 3) u = l1 > (double)p.theta;
     else u = l1x > 0.0 && l1 / l1x > (double)p.theta;
-    if (u && t == 0) slot_early = atomicAdd(p.fb_count, 1);
+    if (t == 0) {
+      if (u) slot_early = atomicAdd(p.fb_count, 1);
+      group_before = atomicOr(p.fb_words + (blk >> 5), my_bits(blk, u));
+    }
   }
 
-  // ---- per-block outputs; the last workgroup to get here compacts the list of flagged blocks
-  if (t == 0) {
-    const int slot0 = u ? ((slot_early < p.capacity) ? slot_early : -2) : -1;
-    p.scales[blk] = a;
-    p.fb_slot[blk] = slot0;
-    if (blk == 0) *p.fb_count_next = 0;   // ready for the next call into this tensor
-    __hip_atomic_store(p.mask + blk, (uint8_t)(u ? 1 : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __threadfence();
-    const int arrived = atomicAdd(p.arrivals, 1);
-    slot_sh = slot0;
-    last_sh = arrived == (int)gridDim.x - 1;
-  }
-  __syncthreads();
-  const int slot = slot_sh;
-  if (last_sh) {      // uniform over the workgroup
-    __threadfence();
-    write_fb_list(p.mask, (int)gridDim.x, p.capacity, p.fb_list, scan_sh, &scan_base_sh);
-    if (t == 0) *p.arrivals = 0;          // ready for the next call
-  }
+  if (kErr) record_block();
   if (slot < 0) return;  // uniform over the workgroup
 
   // ---- step 2: quantize the residual G - a*codes                 (Sec. 4.3)
@@ -493,12 +516,14 @@ __global__ void fill_mask_kernel(uint8_t* mask, int nb, int v) {
 }
 
 // Clears both slot counters: first use of a tensor, or an empty input.
-__global__ void clear_counters_kernel(int32_t* live, int32_t* next, int32_t* arrivals) {
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
+__global__ void clear_counters_kernel(int32_t* live, int32_t* next, int32_t* groups_done,
+                                      unsigned long long* words, int n_words) {
+  if (threadIdx.x == 0) {
     *live = 0;
     *next = 0;
-    *arrivals = 0;
+    *groups_done = 0;
   }
+  for (int i = threadIdx.x; i < n_words; i += blockDim.x) words[i] = 0;
 }
 
 // Tile order -> dense row-major (inspection / tests).
@@ -512,8 +537,8 @@ __global__ void untile_kernel(const int8_t* tiled, int rows, int cols, int nbc, 
 
 hipError_t launch_quantize(const QuantParams& p, hipStream_t st) {
   if (p.clear_both)
-    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, st, p.fb_count, p.fb_count_next,
-                       p.arrivals);
+    hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(256), 0, st, p.fb_count, p.fb_count_next,
+                       p.fb_groups_done, p.fb_words, (p.nbr * p.nbc + 31) / 32);
   const int nb = p.nbr * p.nbc;
   if (nb > 0 && p.crit == 5) {
     if (p.topk <= 0 || p.topk >= nb) {

@@ -38,3 +38,24 @@ def test_default_workload_is_the_config_the_metric_is_quoted_on():
     assert 'default="cfg2"' in src
     # the peaks the roofline figures are priced against: MI355X's published dense INT8 and HBM
     assert bench.INT8_PEAK_TOPS == 5000.0 and bench.HBM_PEAK_GBS == 8000.0
+
+
+def test_traffic_figure_is_tied_to_the_kernel_source(tmp_path, monkeypatch):
+    """roofline.traffic comes from the committed profile summary and only while the GEMM source
+    is the one it was measured on."""
+    import hashlib
+    sys.path.insert(0, ROOT)
+    import bench
+    src = tmp_path / "k.hip"
+    src.write_text("kernel v1")
+    sha = hashlib.sha256(src.read_bytes()).hexdigest()
+    prof = tmp_path / "p.md"
+    prof.write_text(f"# summary\n\ngemm_traffic: workload=wl_a bytes_per_launch=123456 fq_gemm_hip_sha256={sha}\n")
+    monkeypatch.setattr(bench, "GEMM_SOURCE", str(src))
+    monkeypatch.setattr(bench, "TRAFFIC_PROFILE", str(prof))
+    assert bench.measured_gemm_traffic("wl_a") == 123456
+    assert bench.measured_gemm_traffic("wl_b") is None          # another workload
+    src.write_text("kernel v2")
+    assert bench.measured_gemm_traffic("wl_a") is None          # the kernel changed since
+    monkeypatch.setattr(bench, "TRAFFIC_PROFILE", str(tmp_path / "missing.md"))
+    assert bench.measured_gemm_traffic("wl_a") is None
