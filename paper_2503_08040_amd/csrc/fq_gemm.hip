@@ -423,7 +423,17 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
 #pragma unroll
     for (int i = 0; i < G::kSP; ++i) sp[i] = 0.0f;
 
+    int late_b_k = -1;     // B stagers: k-block whose B set is still to be requested (-1: none)
     for (;;) {
+      // The B stagers request their blocks here, two units after the barrier that freed the
+      // ring slot, not right behind it: right after the barrier the four A stagers (one per
+      // SIMD) are blocked on their eight load instructions each, and while they wait for the
+      // address unit to take them, the B stagers, which share their SIMDs, run the last two
+      // units of the item.  With all 64 loads issued at once, both wavefronts of every SIMD sat
+      // blocked and the matrix cores idled for about a fifth of every item.
+      if (late_b_k >= 0)
+        stage_half_block(smain + (int64_t)late_b_k * kBlockBytes, b_ring + (late_b_k & 1) * G::kBSet + soff, lane);
+      late_b_k = -1;
       // ---- the items after this one (all wave-uniform scalar logic)
       const bool n1res = !res && any_flagged(r0);
       const int n1k = n1res ? k : k + 1;
@@ -461,8 +471,12 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
       __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
       __syncthreads();
       if (has2) {
-        if (n2res) stage_item(k + 1, 1, r1, t & 1, false);
-        else stage_item(n2k, 0, r1, t & 1, n2k != n1k);
+        if (stage_a) {
+          if (n2res) stage_item(k + 1, 1, r1, t & 1, false);
+          else stage_item(n2k, 0, r1, t & 1, false);
+        } else if (!n2res && n2k != n1k) {
+          late_b_k = n2k;
+        }
       }
 
       if (active) {
