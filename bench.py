@@ -289,6 +289,39 @@ def overhead_curve(seconds_per_point=0.4, iters=30):
                               "measured points; null: beyond the last measured fraction"}
 
 
+def group_sweep(args):
+    """Sec. 4.5 / Fig. 1b: throughput of the plain block-INT8 GEMM (Eq. (1), no fallback) over the
+    quantization group size g in {32, 64, 128} on square problems, one kernel for all three
+    (fq_gemm_plain), beside the tuned g = 128 kernel (fq_gemm) and the bf16 GEMM."""
+    import torch
+    import paper_2503_08040_amd as fq
+    rows = []
+    g_ = torch.Generator(device="cuda")
+    g_.manual_seed(7)
+    for n in (2048, 4096, 8192):
+        x = torch.randn((n, n), device="cuda", generator=g_, dtype=torch.float32).to(torch.bfloat16)
+        w = (torch.randn((n, n), device="cuda", generator=g_, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+        y = torch.empty((n, n), dtype=torch.bfloat16, device="cuda")
+        ops = 2.0 * n * n * n
+        row = {"M=K=N": n}
+        for g in (32, 64, 128):
+            qx = fq.fq_quantize(x, fq.FQ_CRIT_NONE, 0.0, capacity=0, block=g)
+            qw = fq.fq_quantize(w, fq.FQ_CRIT_NONE, 0.0, capacity=0, block=g)
+            ms = _time_loop(lambda: fq.fq_gemm_plain(fq.FQ_OP_NT, qx, qw, out=y), 0.5, 30)
+            msq = _time_loop(lambda: fq.fq_quantize(x, fq.FQ_CRIT_NONE, 0.0, out=qx), 0.1, 30)
+            row[f"plain_g{g}"] = {"ms_gemm": round(ms, 4), "tops": round(ops / ms / 1e9, 1),
+                                  "ms_quantize": round(msq, 4)}
+            if g == 128:
+                ms = _time_loop(lambda: fq.fq_gemm(fq.FQ_OP_NT, qx, qw, out=y), 0.5, 30)
+                row["tuned_g128"] = {"ms_gemm": round(ms, 4), "tops": round(ops / ms / 1e9, 1)}
+            del qx, qw
+        ms = _time_loop(lambda: torch.matmul(x, w.t(), out=y), 0.5, 30)
+        row["bf16"] = {"ms_gemm": round(ms, 4), "tflops": round(ops / ms / 1e9, 1)}
+        rows.append(row)
+        log(f"[group-sweep] {row}")
+    return {"workload": "square NT, plain block INT8 (no fallback), group size swept", "rows": rows}
+
+
 def backward(args):
     """Sec. 5.1 / 5.3: dY is block-quantized with stochastic rounding, then two plain block GEMMs
     dX = dY W and dW = dY^T X_ctx (X_ctx: the stochastic block-INT8 context stored in forward)."""
@@ -409,6 +442,8 @@ def main():
                          "crossover against the bf16 GEMM; prints one JSON object with a table")
     ap.add_argument("--no-overhead-curve", action="store_true",
                     help="skip the compact config-5 overhead curve (about 10 s)")
+    ap.add_argument("--group-sweep", action="store_true",
+                    help="Fig. 1b: plain block-INT8 GEMM at group sizes 32, 64, 128 on square problems")
     ap.add_argument("--no-mfma-ceiling", action="store_true",
                     help="skip the register-only MFMA throughput probe (about 3 s)")
     ap.add_argument("--backward", action="store_true",
@@ -444,6 +479,9 @@ def main():
         return
     if args.sweep:
         print(json.dumps(sweep(args)), flush=True)
+        return
+    if args.group_sweep:
+        print(json.dumps(group_sweep(args)), flush=True)
         return
     if args.backward:
         print(json.dumps(backward(args)), flush=True)

@@ -32,9 +32,14 @@
  *     stream that is not ordered after the quantize call that filled it.  The only state the
  *     library keeps by itself is a per-device cache of the compute-unit count and of a kernel
  *     attribute, both written once and safe to race on.
- *   - The quantization block is 128 x 128 (FQ_BLOCK); other sizes return
- *     FQ_ERR_BLOCK.  Matrix dimensions need not be multiples of 128: an edge
+ *   - The quantization block is 128 x 128 (FQ_BLOCK), the size the paper settles on
+ *     (Sec. 4.5).  Blocks of 64 x 64 and 32 x 32 are accepted for plain block INT8
+ *     (FQ_CRIT_NONE, round to nearest; no fallback, no transposed residuals), which is what
+ *     the group-size curve of Fig. 1b needs; any other use of them, and any other size,
+ *     returns FQ_ERR_BLOCK.  Matrix dimensions need not be multiples of the block: an edge
  *     block consists of the elements that exist, the rest counts as zero.
+ *     Whatever the block size, codes are stored in 128 x 128 tiles (below); the scale, mask
+ *     and slot grids have one entry per block, nbr = ceil(rows/block) by nbc = ceil(cols/block).
  *
  * Storage order of INT8 codes ("tile order")
  *   Codes are not stored row-major.  A rows x cols matrix is cut into
@@ -70,7 +75,7 @@ typedef enum {
   FQ_OK = 0,
   FQ_ERR_NULL = -1,     /* a required pointer is NULL                          */
   FQ_ERR_SHAPE = -2,    /* negative / inconsistent dimensions or strides       */
-  FQ_ERR_BLOCK = -3,    /* block size other than 128                           */
+  FQ_ERR_BLOCK = -3,    /* unsupported block size, or a block of 64 / 32 with fallback */
   FQ_ERR_ENUM = -4,     /* unknown enum value, or B operand quantized with fallback */
   FQ_ERR_CAPACITY = -5, /* more flagged blocks than `capacity` (fq_qtensor_check) */
   FQ_ERR_HIP = -6,      /* a HIP call failed                                   */
@@ -114,7 +119,7 @@ typedef enum { FQ_OUT_F32 = 0, FQ_OUT_BF16 = 1 } fq_out_dtype;
  */
 typedef struct {
   int32_t rows, cols;    /* shape of the source matrix                           */
-  int32_t block;         /* 128                                                  */
+  int32_t block;         /* 128 (or 64 / 32: plain block INT8, capacity 0)      */
   int32_t capacity;      /* number of residual slots the res_* buffers hold      */
   int32_t criterion;     /* host: fq_criterion of the last fq_quantize into this */
   int32_t epoch;         /* host: fq_quantize calls made into this tensor (library-managed;
@@ -347,6 +352,18 @@ fq_status fq_gemm(fq_op op, const fq_qtensor *A, const fq_qtensor *B, void *C,
                   fq_out_dtype cdt, int64_t ldc, void *hip_stream);
 
 /*
+ * Eq. (1) (no fallback term: A and B quantized with FQ_CRIT_NONE) on the library's plain
+ * kernel: one workgroup per 128 x 128 output tile, per 32 x 32 sub-tile and k-group block/32
+ * matrix instructions into an INT32 tile, then one convert and one fused multiply-add per
+ * element.  It is what fq_gemm runs for blocks of 64 and 32; this entry point also runs it for
+ * block 128, so that the throughput curve over the group size (Sec. 4.5, Fig. 1b) can be
+ * measured on one kernel.  Same results as fq_gemm, bit for bit; arguments and errors as
+ * fq_gemm, plus FQ_ERR_ENUM if A carries fallback blocks.
+ */
+fq_status fq_gemm_plain(fq_op op, const fq_qtensor *A, const fq_qtensor *B, void *C,
+                        fq_out_dtype cdt, int64_t ldc, void *hip_stream);
+
+/*
  * How fq_gemm cuts an rows_out x cols_out output into workgroup tiles (host-only inspection;
  * App. C: the GEMM tile need not equal the quantization block).  The output is covered by
  * 256 x 256 tiles (2 x 2 quantization blocks); when their number would leave the last round of
@@ -360,7 +377,8 @@ fq_status fq_gemm(fq_op op, const fq_qtensor *A, const fq_qtensor *B, void *C,
 fq_status fq_gemm_tile_plan(int32_t rows_out, int32_t cols_out, int32_t compute_units,
                             int32_t plan[3]);
 
-/* The INT32 block product of k-block `k_block` alone (Alg. 1's INT x INT
+/* (With blocks of 64 or 32, k_block counts blocks of that size.)
+ * The INT32 block product of k-block `k_block` alone (Alg. 1's INT x INT
  * product before dequantization): main term (residual_term = 0) or residual
  * term (1; zero for unflagged blocks).  p_out: device int32 [Mout, Nout]
  * row-major, dense.  Same validation as fq_gemm plus 0 <= k_block < nkb. */

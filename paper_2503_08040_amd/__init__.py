@@ -25,7 +25,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfq.so")
 
 EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr", "fq_quantize_topk",
-           "fq_threshold_update", "fq_gemm",
+           "fq_threshold_update", "fq_gemm", "fq_gemm_plain",
            "fq_gemm_debug_partials", "fq_codes_to_rowmajor", "fq_qtensor_check",
            "fq_status_string", "fq_ctx_packed_bytes", "fq_ctx_scales_bytes", "fq_ctx_quantize",
            "fq_ctx_dequantize", "fq_gemm_tile_plan", "fq_glu_forward", "fq_glu_backward", "fq_rmsnorm_forward",
@@ -80,6 +80,8 @@ def lib():
         L.fq_gemm.restype = C.c_int
         L.fq_gemm.argtypes = [C.c_int, C.POINTER(fq_qtensor), C.POINTER(fq_qtensor), C.c_void_p,
                               C.c_int, C.c_int64, C.c_void_p]
+        L.fq_gemm_plain.restype = C.c_int
+        L.fq_gemm_plain.argtypes = L.fq_gemm.argtypes
         L.fq_gemm_debug_partials.restype = C.c_int
         L.fq_gemm_debug_partials.argtypes = [C.c_int, C.POINTER(fq_qtensor), C.POINTER(fq_qtensor),
                                              C.c_int32, C.c_int, C.c_void_p, C.c_void_p]
@@ -146,19 +148,25 @@ class QTensor:
     """Device buffers of one quantized matrix: a torch byte tensor carved up by
     fq_qtensor_bind, plus typed views of its pieces for inspection."""
 
-    def __init__(self, rows, cols, capacity=None, want_transposed=False, device="cuda"):
+    def __init__(self, rows, cols, capacity=None, want_transposed=False, device="cuda",
+                 block=FQ_BLOCK):
         import torch
-        self.rows, self.cols = int(rows), int(cols)
-        self.nbr, self.nbc = -(-self.rows // FQ_BLOCK), -(-self.cols // FQ_BLOCK)
-        self.capacity = self.nbr * self.nbc if capacity is None else int(capacity)
+        self.rows, self.cols, self.block = int(rows), int(cols), int(block)
+        # grids of per-block values (scales, mask, slots); codes are always stored in 128-tiles
+        self.nbr, self.nbc = -(-self.rows // self.block), -(-self.cols // self.block)
+        self.n_tiles = (-(-self.rows // FQ_BLOCK)) * (-(-self.cols // FQ_BLOCK))
+        if capacity is None:
+            capacity = self.nbr * self.nbc if self.block == FQ_BLOCK else 0
+        self.capacity = int(capacity)
         self.want_transposed = bool(want_transposed)
-        nbytes = fq_qtensor_bytes(self.rows, self.cols, self.capacity, self.want_transposed)
+        nbytes = fq_qtensor_bytes(self.rows, self.cols, self.capacity, self.want_transposed,
+                                  self.block)
         if nbytes == 0:
             raise FqError(FQ_ERR_SHAPE, "fq_qtensor_bytes")
         self.storage = torch.empty(nbytes + 256, dtype=torch.uint8, device=device)
         self._base = (self.storage.data_ptr() + 255) & ~255
         self.c = fq_qtensor()
-        _check(lib().fq_qtensor_bind(C.c_void_p(self._base), self.rows, self.cols, FQ_BLOCK,
+        _check(lib().fq_qtensor_bind(C.c_void_p(self._base), self.rows, self.cols, self.block,
                                      self.capacity, int(self.want_transposed), C.byref(self.c)),
                "fq_qtensor_bind")
 
@@ -170,10 +178,9 @@ class QTensor:
     def view(self, field):
         """Typed torch view of one buffer (device memory, no copy)."""
         import torch
-        nb = self.nbr * self.nbc
         spec = {
-            "codes": (torch.int8, (nb, FQ_BLOCK_BYTES), 1),
-            "codes_t": (torch.int8, (nb, FQ_BLOCK_BYTES), 1),
+            "codes": (torch.int8, (self.n_tiles, FQ_BLOCK_BYTES), 1),
+            "codes_t": (torch.int8, (self.n_tiles, FQ_BLOCK_BYTES), 1),
             "scales": (torch.float32, (self.nbr, self.nbc), 4),
             "mask": (torch.uint8, (self.nbr, self.nbc), 1),
             "fb_count": (torch.int32, (1,), 4),
@@ -193,7 +200,7 @@ class QTensor:
 
 
 def fq_quantize(x, crit, theta, out: QTensor = None, capacity=None, want_transposed=False,
-                stream=None) -> QTensor:
+                stream=None, block=FQ_BLOCK) -> QTensor:
     """x: 2-D torch.bfloat16 CUDA tensor with unit column stride."""
     import torch
     assert x.dtype == torch.bfloat16 and x.dim() == 2 and x.is_cuda
@@ -201,8 +208,8 @@ def fq_quantize(x, crit, theta, out: QTensor = None, capacity=None, want_transpo
     rows, cols = x.shape
     ld = x.stride(0) if rows > 1 else max(cols, 1)
     if out is None:
-        out = QTensor(rows, cols, capacity, want_transposed, x.device)
-    _check(lib().fq_quantize(C.c_void_p(x.data_ptr()), rows, cols, ld, FQ_BLOCK, int(crit),
+        out = QTensor(rows, cols, capacity, want_transposed, x.device, block=block)
+    _check(lib().fq_quantize(C.c_void_p(x.data_ptr()), rows, cols, ld, out.block, int(crit),
                              C.c_float(theta), C.byref(out.c), _stream_ptr(stream)), "fq_quantize")
     return out
 
@@ -253,7 +260,12 @@ def gemm_out_shape(op, A: QTensor, B: QTensor):
     raise FqError(FQ_ERR_ENUM, "fq_gemm")
 
 
-def fq_gemm(op, A: QTensor, B: QTensor, out=None, out_dtype=None, stream=None):
+def fq_gemm_plain(op, A: QTensor, B: QTensor, out=None, out_dtype=None, stream=None):
+    """Eq. (1) on the plain kernel (any block size, no fallback); see fq.h."""
+    return fq_gemm(op, A, B, out, out_dtype, stream, _entry="fq_gemm_plain")
+
+
+def fq_gemm(op, A: QTensor, B: QTensor, out=None, out_dtype=None, stream=None, _entry="fq_gemm"):
     """C = A (op) B per Alg. 1; out is a 2-D float32 or bfloat16 CUDA tensor."""
     import torch
     Mo, No = gemm_out_shape(op, A, B)
@@ -262,8 +274,8 @@ def fq_gemm(op, A: QTensor, B: QTensor, out=None, out_dtype=None, stream=None):
     assert out.shape == (Mo, No) and (out.stride(1) == 1 or No <= 1)
     cdt = {torch.float32: FQ_OUT_F32, torch.bfloat16: FQ_OUT_BF16}[out.dtype]
     ldc = out.stride(0) if Mo > 1 else max(No, 1)
-    _check(lib().fq_gemm(int(op), C.byref(A.c), C.byref(B.c), C.c_void_p(out.data_ptr()), cdt,
-                         ldc, _stream_ptr(stream)), "fq_gemm")
+    _check(getattr(lib(), _entry)(int(op), C.byref(A.c), C.byref(B.c), C.c_void_p(out.data_ptr()),
+                                  cdt, ldc, _stream_ptr(stream)), _entry)
     return out
 
 

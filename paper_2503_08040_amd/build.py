@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfq.so")
-SOURCES = ["fq_api.hip", "fq_quantize.hip", "fq_gemm.hip", "fq_ctx.hip"]
+SOURCES = ["fq_api.hip", "fq_quantize.hip", "fq_gemm.hip", "fq_group.hip", "fq_ctx.hip"]
 HEADERS = ["fq_device.h", "fq_kernels.h", os.path.join("..", "..", "include", "fq.h")]
 
 # Packed FP32 VALU instructions are switched off for the device pass (the host

@@ -20,15 +20,20 @@ struct Layout {
       res_scales, total;
 };
 
+inline bool valid_block(int32_t block) { return block == 128 || block == 64 || block == 32; }
+
 bool compute_layout(int32_t rows, int32_t cols, int32_t block, int32_t capacity, int want_t,
                     Layout* L) {
-  if (rows < 0 || cols < 0 || block != FQ_BLOCK || capacity < 0) return false;
-  const int64_t nb = ceil_div(rows, FQ_BLOCK) * ceil_div(cols, FQ_BLOCK);
+  if (rows < 0 || cols < 0 || !valid_block(block) || capacity < 0) return false;
+  // codes are stored in 128 x 128 blocks whatever the group size; the per-group grids are finer
+  const int64_t nb128 = ceil_div(rows, FQ_BLOCK) * ceil_div(cols, FQ_BLOCK);
+  const int64_t nb = ceil_div(rows, block) * ceil_div(cols, block);
   if (capacity > nb || nb > (int64_t)1 << 30) return false;
+  if (block != FQ_BLOCK && capacity != 0) return false;      // fallback needs 128 x 128 blocks
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align256(bytes ? bytes : 1); return o; };
-  L->codes = take((size_t)nb * FQ_BLOCK_BYTES);
-  L->codes_t = want_t ? take((size_t)nb * FQ_BLOCK_BYTES) : (size_t)-1;
+  L->codes = take((size_t)nb128 * FQ_BLOCK_BYTES);
+  L->codes_t = want_t ? take((size_t)nb128 * FQ_BLOCK_BYTES) : (size_t)-1;
   L->scales = take((size_t)nb * 4);
   L->mask = take((size_t)nb);
   L->fb_counters = take(16 + 8 * (size_t)((nb + 31) / 32));
@@ -43,7 +48,8 @@ bool compute_layout(int32_t rows, int32_t cols, int32_t block, int32_t capacity,
 
 fq_status check_qtensor(const fq_qtensor* t) {
   if (!t) return FQ_ERR_NULL;
-  if (t->block != FQ_BLOCK) return FQ_ERR_BLOCK;
+  if (!valid_block(t->block)) return FQ_ERR_BLOCK;
+  if (t->block != FQ_BLOCK && t->capacity != 0) return FQ_ERR_BLOCK;
   if (t->rows < 0 || t->cols < 0 || t->capacity < 0) return FQ_ERR_SHAPE;
   if (!t->codes || !t->scales || !t->mask || !t->fb_count || !t->fb_counters || !t->fb_slot)
     return FQ_ERR_NULL;
@@ -63,9 +69,16 @@ fq_status prepare_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, fq::G
   if (A->criterion < FQ_CRIT_NONE || A->criterion > FQ_CRIT_TOPK) return FQ_ERR_ENUM;
   const bool a_fb = A->criterion != FQ_CRIT_NONE;
   if (a_fb && A->capacity == 0) return FQ_ERR_CAPACITY;
-  const int a_nbr = (int)ceil_div(A->rows, FQ_BLOCK), a_nbc = (int)ceil_div(A->cols, FQ_BLOCK);
-  const int b_nbr = (int)ceil_div(B->rows, FQ_BLOCK), b_nbc = (int)ceil_div(B->cols, FQ_BLOCK);
+  if (A->block != B->block) return FQ_ERR_BLOCK;
+  const int grp = A->block;
+  if (grp != FQ_BLOCK && a_fb) return FQ_ERR_BLOCK;
+  // code blocks are 128 x 128; the scale / slot grids have one entry per group
+  const int a_r128 = (int)ceil_div(A->rows, FQ_BLOCK), a_c128 = (int)ceil_div(A->cols, FQ_BLOCK);
+  const int b_r128 = (int)ceil_div(B->rows, FQ_BLOCK), b_c128 = (int)ceil_div(B->cols, FQ_BLOCK);
+  const int a_nbr = (int)ceil_div(A->rows, grp), a_nbc = (int)ceil_div(A->cols, grp);
+  const int b_nbr = (int)ceil_div(B->rows, grp), b_nbc = (int)ceil_div(B->cols, grp);
   *g = fq::GemmParams{};
+  g->group = grp;
   g->a_scales = A->scales;
   g->a_res_scales = A->res_scales;
   g->a_slot = a_fb ? A->fb_slot : nullptr;
@@ -74,26 +87,29 @@ fq_status prepare_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, fq::G
     case FQ_OP_NT:  // C[M,N] = A[M,K] B[N,K]^T
       if (A->cols != B->cols) return FQ_ERR_SHAPE;
       g->M = A->rows; g->N = B->rows;
-      g->nib = a_nbr; g->njb = b_nbr; g->nkb = a_nbc;
+      g->nib = a_r128; g->njb = b_r128; g->nkb = a_c128;
       g->a_codes = A->codes; g->a_res = A->res_codes; g->a_si = a_nbc; g->a_sk = 1;
       g->b_codes = B->codes; g->b_sj = b_nbc; g->b_sk = 1;
+      g->a_ni = a_nbr; g->a_nk = a_nbc; g->b_nj = b_nbr;
       break;
     case FQ_OP_NN:  // C[M,K] = A[M,N] B[N,K]: B' = B^T
       if (A->cols != B->rows) return FQ_ERR_SHAPE;
       if (!B->codes_t) return FQ_ERR_NULL;
       g->M = A->rows; g->N = B->cols;
-      g->nib = a_nbr; g->njb = b_nbc; g->nkb = a_nbc;
+      g->nib = a_r128; g->njb = b_c128; g->nkb = a_c128;
       g->a_codes = A->codes; g->a_res = A->res_codes; g->a_si = a_nbc; g->a_sk = 1;
       g->b_codes = B->codes_t; g->b_sj = 1; g->b_sk = b_nbc;
+      g->a_ni = a_nbr; g->a_nk = a_nbc; g->b_nj = b_nbc;
       break;
     case FQ_OP_TN:  // C[N,K] = A[M,N]^T B[M,K]: A' = A^T, B' = B^T
       if (A->rows != B->rows) return FQ_ERR_SHAPE;
       if (!A->codes_t || !B->codes_t) return FQ_ERR_NULL;
       if (a_fb && !A->res_codes_t) return FQ_ERR_NULL;
       g->M = A->cols; g->N = B->cols;
-      g->nib = a_nbc; g->njb = b_nbc; g->nkb = a_nbr;
+      g->nib = a_c128; g->njb = b_c128; g->nkb = a_r128;
       g->a_codes = A->codes_t; g->a_res = A->res_codes_t; g->a_si = 1; g->a_sk = a_nbc;
       g->b_codes = B->codes_t; g->b_sj = 1; g->b_sk = b_nbc;
+      g->a_ni = a_nbc; g->a_nk = a_nbr; g->b_nj = b_nbc;
       break;
   }
   return FQ_OK;
@@ -113,7 +129,8 @@ size_t fq_qtensor_bytes(int32_t rows, int32_t cols, int32_t block, int32_t capac
 fq_status fq_qtensor_bind(void* base, int32_t rows, int32_t cols, int32_t block,
                           int32_t capacity, int want_transposed, fq_qtensor* out) {
   if (!base || !out) return FQ_ERR_NULL;
-  if (block != FQ_BLOCK) return FQ_ERR_BLOCK;
+  if (!valid_block(block)) return FQ_ERR_BLOCK;
+  if (block != FQ_BLOCK && capacity != 0) return FQ_ERR_BLOCK;
   Layout L;
   if (!compute_layout(rows, cols, block, capacity, want_transposed, &L)) return FQ_ERR_SHAPE;
   if ((uintptr_t)base & 255) return FQ_ERR_SHAPE;
@@ -139,12 +156,16 @@ fq_status quantize_impl(const void* x_bf16, int32_t rows, int32_t cols, int64_t 
                         fq_criterion crit, float theta, int stochastic, uint64_t seed,
                         int32_t topk, fq_qtensor* out, void* hip_stream) {
   if (!out) return FQ_ERR_NULL;
-  if (block != FQ_BLOCK) return FQ_ERR_BLOCK;
+  if (!valid_block(block)) return FQ_ERR_BLOCK;
+  // groups of 64 and 32: plain round-to-nearest block INT8 only (the fallback scheme and the
+  // other selectors are defined on the paper's 128 x 128 blocks)
+  if (block != FQ_BLOCK && (crit != FQ_CRIT_NONE || stochastic)) return FQ_ERR_BLOCK;
   if (rows < 0 || cols < 0 || ld < cols) return FQ_ERR_SHAPE;
   if (crit < FQ_CRIT_NONE || crit > FQ_CRIT_TOPK) return FQ_ERR_ENUM;
   fq_status s = check_qtensor(out);
   if (s != FQ_OK) return s;
   if (out->rows != rows || out->cols != cols) return FQ_ERR_SHAPE;
+  if (out->block != block) return FQ_ERR_BLOCK;
   const bool empty = rows == 0 || cols == 0;
   if (!empty && !x_bf16) return FQ_ERR_NULL;
   if (crit == FQ_CRIT_TOPK) {
@@ -158,7 +179,8 @@ fq_status quantize_impl(const void* x_bf16, int32_t rows, int32_t cols, int64_t 
   fq::QuantParams p{};
   p.x = static_cast<const uint16_t*>(x_bf16);
   p.rows = rows; p.cols = cols; p.ld = ld;
-  p.nbr = (int)ceil_div(rows, FQ_BLOCK); p.nbc = (int)ceil_div(cols, FQ_BLOCK);
+  p.nbr = (int)ceil_div(rows, block); p.nbc = (int)ceil_div(cols, block);
+  p.group = block;
   p.vec_ok = (((uintptr_t)x_bf16 & 15) == 0 && (ld % 8) == 0) ? 1 : 0;
   p.crit = (int)crit; p.theta = theta; p.topk = topk; p.capacity = out->capacity;
   p.stochastic = stochastic; p.seed = seed;
@@ -187,6 +209,15 @@ fq_status quantize_impl(const void* x_bf16, int32_t rows, int32_t cols, int64_t 
   p.fb_list = out->fb_list; p.fb_slot = out->fb_slot;
   p.res_codes = out->res_codes; p.res_codes_t = out->res_codes_t; p.res_scales = out->res_scales;
   out->criterion = (int32_t)crit;
+  p.fb_count_base = out->fb_counters;
+  if (block != FQ_BLOCK) {
+    // no fallback, nothing is counted: the counters are cleared and the tensor stays "fresh"
+    out->fb_count = out->fb_counters;
+    out->epoch = 0;
+    if (fq::launch_quantize_group(p, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
+      return FQ_ERR_HIP;
+    return FQ_OK;
+  }
   if (fq::launch_quantize(p, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
     return FQ_ERR_HIP;
   return FQ_OK;
@@ -404,8 +435,9 @@ fq_status fq_rmsnorm_backward_static(const void* dy_bf16, int64_t ld_dy, const u
                              dx_bf16, ldo, dw, ws, n_parts, hip_stream);
 }
 
-fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,
-                  int64_t ldc, void* hip_stream) {
+namespace {
+fq_status gemm_impl(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,
+                    int64_t ldc, bool plain, void* hip_stream) {
   fq::GemmParams g;
   fq_status s = prepare_gemm(op, A, B, &g);
   if (s != FQ_OK) return s;
@@ -416,9 +448,22 @@ fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, f
   g.c = C; g.ldc = ldc; g.out_bf16 = cdt == FQ_OUT_BF16;
   const int64_t esz = g.out_bf16 ? 2 : 4;
   g.vec_ok = (((uintptr_t)C & 15) == 0 && (ldc * esz) % 16 == 0) ? 1 : 0;
-  if (fq::launch_gemm(g, false, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
-    return FQ_ERR_HIP;
-  return FQ_OK;
+  const hipError_t e = (plain || g.group != FQ_BLOCK)
+                           ? fq::launch_gemm_group(g, false, static_cast<hipStream_t>(hip_stream))
+                           : fq::launch_gemm(g, false, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+}
+}  // namespace
+
+fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,
+                  int64_t ldc, void* hip_stream) {
+  return gemm_impl(op, A, B, C, cdt, ldc, false, hip_stream);
+}
+
+fq_status fq_gemm_plain(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C,
+                        fq_out_dtype cdt, int64_t ldc, void* hip_stream) {
+  if (A && A->criterion != FQ_CRIT_NONE) return FQ_ERR_ENUM;    // Eq. (1) only: no fallback term
+  return gemm_impl(op, A, B, C, cdt, ldc, true, hip_stream);
 }
 
 fq_status fq_gemm_tile_plan(int32_t rows_out, int32_t cols_out, int32_t compute_units,
@@ -438,14 +483,16 @@ fq_status fq_gemm_debug_partials(fq_op op, const fq_qtensor* A, const fq_qtensor
   fq::GemmParams g;
   fq_status s = prepare_gemm(op, A, B, &g);
   if (s != FQ_OK) return s;
-  if (k_block < 0 || k_block >= g.nkb) return FQ_ERR_SHAPE;
+  if (k_block < 0 || k_block >= g.a_nk) return FQ_ERR_SHAPE;
   if (g.M == 0 || g.N == 0) return FQ_OK;
   if (!p_out) return FQ_ERR_NULL;
   g.c = p_out; g.ldc = g.N; g.out_bf16 = 0;
   g.vec_ok = (((uintptr_t)p_out & 15) == 0 && (g.N % 4) == 0) ? 1 : 0;
   g.debug_k = k_block; g.debug_residual = residual_term ? 1 : 0;
-  if (fq::launch_gemm(g, true, static_cast<hipStream_t>(hip_stream)) != hipSuccess)
-    return FQ_ERR_HIP;
+  const hipError_t e = g.group != FQ_BLOCK
+                           ? fq::launch_gemm_group(g, true, static_cast<hipStream_t>(hip_stream))
+                           : fq::launch_gemm(g, true, static_cast<hipStream_t>(hip_stream));
+  if (e != hipSuccess) return FQ_ERR_HIP;
   return FQ_OK;
 }
 
@@ -477,7 +524,7 @@ const char* fq_status_string(fq_status s) {
     case FQ_OK: return "ok";
     case FQ_ERR_NULL: return "a required pointer is NULL";
     case FQ_ERR_SHAPE: return "invalid or inconsistent shape";
-    case FQ_ERR_BLOCK: return "unsupported block size (128 only)";
+    case FQ_ERR_BLOCK: return "unsupported block size (128; 64 or 32 for plain block INT8 without fallback)";
     case FQ_ERR_ENUM: return "invalid enum value or B operand quantized with fallback";
     case FQ_ERR_CAPACITY: return "more flagged blocks than residual slots";
     case FQ_ERR_HIP: return "HIP call failed";

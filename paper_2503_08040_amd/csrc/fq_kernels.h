@@ -9,7 +9,8 @@ struct QuantParams {
   const uint16_t* x;   // bf16 bits, row-major [rows, ld]
   int rows, cols;
   int64_t ld;
-  int nbr, nbc;
+  int nbr, nbc;        // scale / mask / slot grid: ceil(rows / group) x ceil(cols / group)
+  int group;           // quantization group edge: 128, or 64 / 32 (plain block INT8 only)
   int vec_ok;          // base 16-byte aligned and ld % 8 == 0: full blocks use 16-byte loads
   int crit;
   int stochastic;      // 1: stochastic rounding with `seed` (crit must be 0)
@@ -21,6 +22,7 @@ struct QuantParams {
   int8_t* codes_t;     // nullptr: no transposed copies
   float* scales;
   uint8_t* mask;
+  int32_t* fb_count_base;  // the tensor's counter buffer (groups < 128: cleared, nothing counted)
   int32_t* fb_count;       // live slot counter of this call (zero on entry)
   int32_t* fb_count_next;  // counter of the next call: cleared by this call
   int32_t* fb_groups_done;       // groups of 32 blocks whose decisions are all recorded (zero between calls)
@@ -54,7 +56,9 @@ struct GemmParams {
   int out_bf16;
   int vec_ok;                 // C base and row pitch allow 16-byte stores
   int n_main, main_tj, tail_tj;   // tile plan, filled in by launch_gemm
-  int debug_k;                // debug mode: the single k-block to evaluate
+  int group;                  // quantization group edge (128, 64, 32)
+  int a_ni, a_nk, b_nj;       // extents of the scale grids along i, k (A) and j (B), in groups
+  int debug_k;                // debug mode: the single k-block (k-group) to evaluate
   int debug_residual;         // debug mode: 0 main term, 1 residual term
 };
 
@@ -125,6 +129,9 @@ struct RmsParams {
 hipError_t launch_quantize(const QuantParams& p, hipStream_t st);
 hipError_t launch_untile(const int8_t* tiled, int rows, int cols, int8_t* dense, hipStream_t st);
 hipError_t launch_gemm(const GemmParams& p, bool debug, hipStream_t st);
+// groups of 32 / 64 (and the plain 128 kernel): fq_group.hip
+hipError_t launch_quantize_group(const QuantParams& p, hipStream_t st);
+hipError_t launch_gemm_group(const GemmParams& p, bool debug, hipStream_t st);
 // out = {workgroups with 2x2-block tiles, tile columns they cover, 1x3-block tile columns};
 // cus <= 0: the current device's compute units (or FQ_GEMM_CUS).
 void gemm_tile_plan(int nib, int njb, int cus, int out[3]);
