@@ -442,6 +442,9 @@ def main():
                          "crossover against the bf16 GEMM; prints one JSON object with a table")
     ap.add_argument("--no-overhead-curve", action="store_true",
                     help="skip the compact config-5 overhead curve (about 10 s)")
+    ap.add_argument("--pipeline-probe", action="store_true",
+                    help="run the register-resident pipeline probe (cycles per unit and clock of the "
+                         "MFMA + dequantization mix; about 15 s) and print its table as one JSON object")
     ap.add_argument("--group-sweep", action="store_true",
                     help="Fig. 1b: plain block-INT8 GEMM at group sizes 32, 64, 128 on square problems")
     ap.add_argument("--no-mfma-ceiling", action="store_true",
@@ -479,6 +482,16 @@ def main():
         return
     if args.sweep:
         print(json.dumps(sweep(args)), flush=True)
+        return
+    if args.pipeline_probe:
+        import subprocess
+        tool = os.path.join(ROOT, "paper_2503_08040_amd", "pipeline_probe")
+        r = subprocess.run([tool], capture_output=True, text=True, timeout=300)
+        if r.returncode != 0:
+            raise SystemExit(f"pipeline_probe failed: {r.stderr}")
+        print(json.dumps({"tool": "pipeline_probe",
+                          "modes": [json.loads(ln) for ln in r.stdout.splitlines() if ln.startswith("{")]}),
+              flush=True)
         return
     if args.group_sweep:
         print(json.dumps(group_sweep(args)), flush=True)

@@ -15,7 +15,7 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Wall", "-Wno-unused-command-line-argument"]
 
 
-TOOLS = ["mfma_ceiling", "group_size_probe"]
+TOOLS = ["mfma_ceiling", "pipeline_probe"]
 TOOL_BIN = os.path.join(HERE, "mfma_ceiling")
 
 

@@ -1,0 +1,252 @@
+// pipeline_probe -- the inner pipeline of the block GEMM in the cycle domain (measurement support).
+//
+// Paper: Sec. 4.2 Eq. (1) (INT8 block product dequantized per block on the general-purpose ALUs),
+// Sec. 4.5 / Fig. 1b (that dequantization is what limits small groups).
+//
+// Register-resident loops, 2 wavefronts per SIMD on every compute unit (or 1), random INT8
+// operands, every instruction of the loop body written in inline assembly so that the stream is
+// exactly what is listed: per MFMA "slot" one v_mfma_i32_16x16x64_i8 (or v_mfma_i32_32x32x32_i8),
+// NF v_fmac_f32 and NC v_cvt_f32_i32, optionally R ds_read_b128 per 32 x 32 x 128 unit, operands
+// in architectural or accumulation registers.  Each wavefront reads the shader clock counter
+// (s_memtime) and the constant 100 MHz counter (s_memrealtime) around its loop, so every mode is
+// reported as cycles per unit AND as the clock the GPU ran at: the part is power-managed, and a
+// time-domain figure alone cannot tell "more cycles" from "lower clock".
+// Prints one JSON object per mode, one per line.
+#include <hip/hip_runtime.h>
+#include <chrono>
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+#define CHECK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { fprintf(stderr, "%s: %s\n", #x, hipGetErrorString(e_)); exit(1);} } while (0)
+
+__device__ __forceinline__ uint64_t memtime_now() {
+  uint64_t t; asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)); return t; }
+__device__ __forceinline__ uint64_t realtime_now() {
+  uint64_t t; asm volatile("s_memrealtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)); return t; }
+
+constexpr int kUnits = 4;
+
+// AB: 0 A/B fragments in VGPRs, 1 in AGPRs.  NF/NC: FMAs / converts per MFMA.  R: ds_read_b128 per unit.
+// SS: 1 = scale from an SGPR.  CV: 1 = the first MFMA of a pair also reads C from registers.
+template <int AB, int NF, int NC, int R, int SS, int CV, int kThreads>
+__global__ __launch_bounds__(kThreads, 1) void probe(const v4i* in, float* out, uint64_t* stamps, float s, int trips) {
+  extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int i = 0; i < 16; ++i)
+    *reinterpret_cast<v4i*>(lds + w * 16384 + i * 1024 + lane * 16) = in[(i & 7) * 512 + (threadIdx.x & 511)];
+  __syncthreads();
+  v4i fr[2][8];   // [buffer][a0..a3, b0..b3]
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    v4i v = in[i * 512 + (threadIdx.x & 511)];
+    if (AB) { asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(fr[0][i][0]) : "v"(v[0]));
+              asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(fr[0][i][1]) : "v"(v[1]));
+              asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(fr[0][i][2]) : "v"(v[2]));
+              asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(fr[0][i][3]) : "v"(v[3])); fr[1][i] = fr[0][i]; }
+    else { fr[0][i] = v; fr[1][i] = v; }
+  }
+  float acc[kUnits][16];
+#pragma unroll
+  for (int u = 0; u < kUnits; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[u][i] = 0.0f;
+  v4i P[2][4];
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) P[c][q] = v4i{0, 0, 0, 0};
+  float T[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  float sv = s;
+  asm volatile("" : "+v"(sv));
+  const unsigned lds_addr = (unsigned)(w * 16384 + lane * 16);
+  __syncthreads();
+  const uint64_t t0 = memtime_now(), r0 = realtime_now();
+  for (int it = 0; it < trips; ++it) {
+#pragma unroll
+    for (int u = 0; u < kUnits; ++u) {
+      const int cur = u & 1, nxt = cur ^ 1;
+      if (R > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {
+        const int ks = n >> 2, q = n & 3;
+        const int ai = (2 * ks + (q >> 1)) & 3, bi = 4 + ((2 * ks + (q & 1)) & 3);
+        if (AB) {
+          if (ks || CV) asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+v"(P[cur][q]) : "a"(fr[cur][ai]), "a"(fr[cur][bi]));
+          else asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, 0" : "=v"(P[cur][q]) : "a"(fr[cur][ai]), "a"(fr[cur][bi]));
+        } else {
+          if (ks || CV) asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+v"(P[cur][q]) : "v"(fr[cur][ai]), "v"(fr[cur][bi]));
+          else asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, 0" : "=v"(P[cur][q]) : "v"(fr[cur][ai]), "v"(fr[cur][bi]));
+        }
+        if (n < R) {
+          if (AB) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=a"(fr[nxt][n]) : "v"(lds_addr), "n"(n * 1024));
+          else asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(fr[nxt][n]) : "v"(lds_addr), "n"(n * 1024));
+        }
+        const int pu = (u + kUnits - 1) % kUnits;
+#pragma unroll
+        for (int i = 0; i < NF; ++i) {
+          const int e = (NF * n + i) & 15;
+          if (SS) asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[pu][e]) : "s"(s), "v"(T[i]));
+          else asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[pu][e]) : "v"(T[i]), "v"(sv));
+        }
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+          const int e = (NC * n + i) & 15;
+          asm volatile("v_cvt_f32_i32 %0, %1" : "=v"(T[i]) : "v"(P[nxt][e >> 2][e & 3]));
+        }
+      }
+    }
+  }
+  const uint64_t t1 = memtime_now(), r1 = realtime_now();
+  float r = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) r += T[i];
+#pragma unroll
+  for (int u = 0; u < kUnits; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r += acc[u][i];
+#pragma unroll
+  for (int c = 0; c < 2; ++c)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) r += (float)(P[c][q][i]);
+  if (!AB) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) r += (float)fr[c][q][0];
+  } else {
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) { int x; asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(fr[c][q][0])); r += (float)x; }
+  }
+  out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+  if (threadIdx.x == 0) { stamps[2 * blockIdx.x] = t1 - t0; stamps[2 * blockIdx.x + 1] = r1 - r0; }
+}
+
+
+// One trip = 2 pairs of units (4 units): chains X and Y interleaved, 4 MFMAs each (K = 128), and the
+// dequantization of the previous pair's tiles spread over the 8 MFMA slots: NV instructions per slot
+// (half FMAs, half converts).  CH: 1 = the two chains interleave, 0 = each chain's MFMAs back to back.
+template <int NV, int CH, int kThreads>
+__global__ __launch_bounds__(kThreads, 1) void probe32(const v4i* in, float* out, uint64_t* stamps, float s, int trips) {
+  v4i fa[4], fb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { fa[i] = in[i * 512 + (threadIdx.x & 511)]; fb[i] = in[(4 + i) * 512 + (threadIdx.x & 511)]; }
+  float acc[4][16];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[u][i] = 0.0f;
+  v16i P[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c) P[c] = v16i{0};
+  float T[4] = {0, 0, 0, 0};
+  float sv = s;
+  asm volatile("" : "+v"(sv));
+  const uint64_t t0 = memtime_now(), r0 = realtime_now();
+  for (int it = 0; it < trips; ++it) {
+#pragma unroll
+    for (int pr = 0; pr < 2; ++pr) {          // pair of units: tiles P[2pr], P[2pr+1]; dequantizes the other pair
+      const int x = 2 * pr, y = 2 * pr + 1, ox = 2 * (pr ^ 1), oy = ox + 1;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {
+        const int chain = CH ? (n & 1) : (n >> 2), step = CH ? (n >> 1) : (n & 3);
+        const int t = chain ? y : x;
+        if (step) asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, %0" : "+v"(P[t]) : "v"(fa[step]), "v"(fb[(step + chain) & 3]));
+        else asm volatile("v_mfma_i32_32x32x32_i8 %0, %1, %2, 0" : "=v"(P[t]) : "v"(fa[step]), "v"(fb[(step + chain) & 3]));
+        constexpr int nf = NV / 2, nc = NV - NV / 2;
+        const int ot = (n < 4) ? ox : oy;     // tile being folded in this slot
+#pragma unroll
+        for (int i = 0; i < nf; ++i) {
+          const int e = (nf * n + i) & 15;
+          asm volatile("v_fmac_f32 %0, %1, %2" : "+v"(acc[ot][e]) : "v"(T[i]), "v"(sv));
+        }
+#pragma unroll
+        for (int i = 0; i < nc; ++i) {
+          const int e = (nc * n + i) & 15;
+          asm volatile("v_cvt_f32_i32 %0, %1" : "=v"(T[i]) : "v"(P[ot][e]));
+        }
+      }
+    }
+  }
+  const uint64_t t1 = memtime_now(), r1 = realtime_now();
+  float r = T[0] + T[1] + T[2] + T[3];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r += acc[u][i] + (float)P[u][i];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+  if (threadIdx.x == 0) { stamps[2 * blockIdx.x] = t1 - t0; stamps[2 * blockIdx.x + 1] = r1 - r0; }
+}
+
+
+static int g_cus;
+static v4i* g_in; static float* g_out; static uint64_t* g_stamps;
+
+template <typename K>
+static void time_kernel(K k, int threads, int units_per_trip, const char* name, const char* desc) {
+  const int trips = 2048;
+  const int ldsb = 128 * 1024;      // one workgroup per compute unit
+  CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, ldsb));
+  auto launch = [&] { hipLaunchKernelGGL(k, dim3(g_cus), dim3(threads), ldsb, 0, g_in, g_out, g_stamps, 1e-12f, trips); };
+  const auto t0 = std::chrono::steady_clock::now();
+  do { for (int r = 0; r < 8; ++r) launch(); CHECK(hipDeviceSynchronize()); }
+  while (std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() < 0.4);
+  hipEvent_t e0, e1; CHECK(hipEventCreate(&e0)); CHECK(hipEventCreate(&e1));
+  const int launches = 20;
+  CHECK(hipEventRecord(e0));
+  for (int r = 0; r < launches; ++r) launch();
+  CHECK(hipEventRecord(e1)); CHECK(hipEventSynchronize(e1));
+  float ms; CHECK(hipEventElapsedTime(&ms, e0, e1));
+  std::vector<uint64_t> st(2 * g_cus);
+  CHECK(hipMemcpy(st.data(), g_stamps, st.size() * 8, hipMemcpyDeviceToHost));
+  double mt = 0, rt = 0;
+  for (int i = 0; i < g_cus; ++i) { mt += st[2 * i]; rt += st[2 * i + 1]; }
+  const double units = (double)trips * units_per_trip;
+  const double wps = threads / 256;                           // wavefronts per SIMD
+  const double ns_simd_unit = ms / launches * 1e6 / units / wps;
+  const double mhz = mt / rt * 100.0;
+  const double tops = units * (double)g_cus * (threads / 64) * 2.0 * 32 * 32 * 128 / (ms / launches * 1e-3) / 1e12;
+  printf("{\"mode\": \"%s\", \"what\": \"%s\", \"waves_per_simd\": %d, \"ns_per_simd_unit\": %.1f, "
+         "\"cycles_per_simd_unit\": %.1f, \"clock_mhz\": %.0f, \"chip_tops\": %.0f}\n",
+         name, desc, threads / 256, ns_simd_unit, ns_simd_unit * mhz * 1e-3, mhz, tops);
+  fflush(stdout);
+}
+
+int main() {
+  hipDeviceProp_t prop; CHECK(hipGetDeviceProperties(&prop, 0));
+  g_cus = prop.multiProcessorCount;
+  const size_t n = 8 * 512;
+  std::vector<v4i> h(n);
+  srand(1);
+  for (size_t i = 0; i < n; ++i) for (int c = 0; c < 4; ++c) {
+    uint32_t v = 0; for (int bb = 0; bb < 4; ++bb) v |= (uint32_t)(((rand() % 255) - 127) & 0xFF) << (8 * bb);
+    h[i][c] = (int)v; }
+  CHECK(hipMalloc(&g_in, n * sizeof(v4i))); CHECK(hipMalloc(&g_out, (size_t)g_cus * 512 * 4)); CHECK(hipMalloc(&g_stamps, g_cus * 16));
+  CHECK(hipMemcpy(g_in, h.data(), n * sizeof(v4i), hipMemcpyHostToDevice));
+  // a "unit" is a 32 x 32 x 128 multiply-accumulate of one wavefront: 8 MFMA 16x16x64 or 4 MFMA 32x32x32
+  //                 AB NF NC R SS CV threads
+  time_kernel(probe<0, 0, 0, 0, 0, 0, 512>, 512, kUnits, "mfma16_only", "8 MFMA 16x16x64 per unit, nothing else");
+  time_kernel(probe<0, 1, 1, 0, 0, 0, 512>, 512, kUnits, "mfma16_1fma_1cvt", "per MFMA: 1 FMA + 1 convert (half the exact dequantization)");
+  time_kernel(probe<0, 2, 2, 0, 0, 0, 512>, 512, kUnits, "mfma16_2fma_2cvt", "per MFMA: 2 FMA + 2 converts = the exact dequantization of Eq. (1) at group 128");
+  time_kernel(probe<0, 3, 3, 0, 0, 0, 512>, 512, kUnits, "mfma16_3fma_3cvt", "per MFMA: 3 FMA + 3 converts");
+  time_kernel(probe<0, 4, 0, 0, 0, 0, 512>, 512, kUnits, "mfma16_4fma", "per MFMA: 4 FMA");
+  time_kernel(probe<0, 0, 4, 0, 0, 0, 512>, 512, kUnits, "mfma16_4cvt", "per MFMA: 4 converts");
+  time_kernel(probe<0, 8, 0, 0, 0, 0, 512>, 512, kUnits, "mfma16_8fma", "per MFMA: 8 FMA (the mix of group 64)");
+  time_kernel(probe<1, 2, 2, 0, 0, 0, 512>, 512, kUnits, "mfma16_2fma_2cvt_ab_in_agpr", "exact dequantization, A/B operands in accumulation registers");
+  time_kernel(probe<0, 2, 2, 0, 1, 0, 512>, 512, kUnits, "mfma16_2fma_2cvt_sgpr_scale", "exact dequantization, scale from a scalar register");
+  time_kernel(probe<0, 2, 2, 3, 0, 0, 512>, 512, kUnits, "mfma16_2fma_2cvt_3reads", "exact dequantization + 3 ds_read_b128 per unit (what the GEMM's wavefront tile needs)");
+  time_kernel(probe<0, 0, 0, 3, 0, 0, 512>, 512, kUnits, "mfma16_3reads", "MFMA + 3 ds_read_b128 per unit, no dequantization");
+  time_kernel(probe<0, 2, 2, 0, 0, 0, 256>, 256, kUnits, "mfma16_2fma_2cvt_1wave", "exact dequantization, one wavefront per SIMD");
+  time_kernel(probe32<0, 1, 512>, 512, 4, "mfma32_only", "4 MFMA 32x32x32 per unit, nothing else");
+  time_kernel(probe32<6, 1, 512>, 512, 4, "mfma32_6valu", "per MFMA 32x32x32: 3 FMA + 3 converts");
+  time_kernel(probe32<8, 1, 512>, 512, 4, "mfma32_4fma_4cvt", "per MFMA 32x32x32: 4 FMA + 4 converts = the exact dequantization");
+  time_kernel(probe32<10, 1, 512>, 512, 4, "mfma32_10valu", "per MFMA 32x32x32: 5 FMA + 5 converts");
+  return 0;
+}
