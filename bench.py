@@ -322,6 +322,50 @@ def group_sweep(args):
     return {"workload": "square NT, plain block INT8 (no fallback), group size swept", "rows": rows}
 
 
+def gemm_ablation(args):
+    """Times fq_gemm on the workload with the library and with each ablation build of it (one
+    component of the k-loop removed or added, see csrc/fq_gemm.hip), each in a process of its
+    own because a process loads one build.  The ablation builds compute wrong products."""
+    import subprocess
+    from paper_2503_08040_amd import build as hip_build
+    rows = []
+    for name in ["library"] + list(hip_build.ABLATIONS):
+        env = dict(os.environ)
+        if name != "library":
+            path = hip_build.ablation_lib(name)
+            if not os.path.exists(path):
+                raise SystemExit(f"{path} is missing: python -m paper_2503_08040_amd.build")
+            env["FQ_LIBRARY"] = path
+        r = subprocess.run([sys.executable, os.path.abspath(__file__), "--gemm-only",
+                            "--workload", args.workload, "--steps", str(args.steps)],
+                           capture_output=True, text=True, env=env, timeout=600)
+        if r.returncode != 0:
+            raise SystemExit(f"ablation {name} failed: {r.stderr[-2000:]}")
+        row = json.loads(r.stdout.strip().splitlines()[-1])
+        row["build"] = name
+        rows.append(row)
+        log(f"[gemm-ablation] {row}")
+    base = rows[0]["ms_gemm"]
+    for row in rows:
+        row["vs_library"] = round(row["ms_gemm"] / base, 4)
+    return {"workload": args.workload, "rows": rows}
+
+
+def gemm_only(args):
+    """fq_gemm alone on the workload: milliseconds per launch (HIP events, after a warm-up)."""
+    import torch
+    import paper_2503_08040_amd as fq
+    wl = make_workload(args.workload)
+    x = torch.from_numpy(wl.X.view(np.int16)).cuda().view(torch.bfloat16)
+    w = torch.from_numpy(wl.W.view(np.int16)).cuda().view(torch.bfloat16)
+    qx = fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, wl.theta)
+    qw = fq.fq_quantize(w, fq.FQ_CRIT_NONE, 0.0, capacity=0)
+    y = torch.empty((wl.M, wl.N), dtype=torch.bfloat16, device="cuda")
+    ms = _time_loop(lambda: fq.fq_gemm(fq.FQ_OP_NT, qx, qw, out=y), 1.0, max(args.steps, 50))
+    ops = 2.0 * wl.M * wl.N * wl.K
+    return {"ms_gemm": round(ms, 4), "tops": round(ops / ms / 1e9, 1)}
+
+
 def backward(args):
     """Sec. 5.1 / 5.3: dY is block-quantized with stochastic rounding, then two plain block GEMMs
     dX = dY W and dW = dY^T X_ctx (X_ctx: the stochastic block-INT8 context stored in forward)."""
@@ -445,6 +489,11 @@ def main():
     ap.add_argument("--pipeline-probe", action="store_true",
                     help="run the register-resident pipeline probe (cycles per unit and clock of the "
                          "MFMA + dequantization mix; about 15 s) and print its table as one JSON object")
+    ap.add_argument("--gemm-ablation", action="store_true",
+                    help="time fq_gemm with each ablation build of the library (a component of the "
+                         "k-loop removed or added); prints one JSON object with a table")
+    ap.add_argument("--gemm-only", action="store_true",
+                    help="time fq_gemm alone on the workload and print {ms_gemm, tops}")
     ap.add_argument("--group-sweep", action="store_true",
                     help="Fig. 1b: plain block-INT8 GEMM at group sizes 32, 64, 128 on square problems")
     ap.add_argument("--no-mfma-ceiling", action="store_true",
@@ -495,6 +544,12 @@ def main():
         return
     if args.group_sweep:
         print(json.dumps(group_sweep(args)), flush=True)
+        return
+    if args.gemm_only:
+        print(json.dumps(gemm_only(args)), flush=True)
+        return
+    if args.gemm_ablation:
+        print(json.dumps(gemm_ablation(args)), flush=True)
         return
     if args.backward:
         print(json.dumps(backward(args)), flush=True)

@@ -22,7 +22,8 @@ FQ_OP_NT, FQ_OP_NN, FQ_OP_TN = 0, 1, 2
 FQ_OUT_F32, FQ_OUT_BF16 = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libfq.so")
+# FQ_LIBRARY: another build of the same library to load instead (the benchmark's ablation builds)
+LIB_PATH = os.environ.get("FQ_LIBRARY") or os.path.join(_HERE, "libfq.so")
 
 EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr", "fq_quantize_topk",
            "fq_threshold_update", "fq_gemm", "fq_gemm_plain",

@@ -36,6 +36,41 @@ def build_tools() -> list:
     return out
 
 
+# Ablation builds of the GEMM kernel (measurement support, see the switches at the top of
+# csrc/fq_gemm.hip): whole libraries, libfq_ablate_<name>.so, loaded instead of libfq.so when the
+# environment variable FQ_LIBRARY names one.  They compute wrong products on purpose.
+ABLATIONS = {
+    "no_dma": ["-DFQ_ABLATE_NO_DMA"],
+    "no_multiply": ["-DFQ_ABLATE_NO_MULTIPLY"],
+    "no_dequant": ["-DFQ_ABLATE_NO_DEQUANT"],
+    "extra_salu_40": ["-DFQ_ABLATE_EXTRA_SALU=40"],
+    "extra_salu_120": ["-DFQ_ABLATE_EXTRA_SALU=120"],
+    "one_stager": ["-DFQ_ABLATE_ONE_STAGER"],
+}
+
+
+def ablation_lib(name: str) -> str:
+    return os.path.join(HERE, f"libfq_ablate_{name}.so")
+
+
+def build_ablations(names=None, jobs: int = 6) -> list:
+    """Compile the ablation libraries (in parallel: each is a full build of the library)."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    names = list(ABLATIONS) if names is None else list(names)
+
+    def one(name):
+        cmd = [hipcc] + HIPCC_FLAGS + ["-Wno-unused-but-set-variable", "-Wno-unused-variable"] + \
+              ABLATIONS[name] + ["-o", ablation_lib(name)] + [os.path.join(CSRC, f) for f in SOURCES]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"hipcc failed ({name}):\n{r.stderr}")
+        return ablation_lib(name)
+
+    with ThreadPoolExecutor(max_workers=max(1, jobs)) as ex:
+        return list(ex.map(one, names))
+
+
 def stale() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -63,3 +98,4 @@ def build(force: bool = True, extra_flags=()) -> str:
 if __name__ == "__main__":
     print(build())
     print(build_tools())
+    print(build_ablations())

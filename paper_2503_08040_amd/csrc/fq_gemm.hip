@@ -42,6 +42,14 @@
 #include "fq_device.h"
 #include "fq_kernels.h"
 
+// Ablation switches (measurement support; the library itself is built with none of them, and a
+// build with one computes wrong products on purpose).  Each removes or adds one component of the
+// k-loop so that its cost can be read off a timing of the whole kernel:
+//   FQ_ABLATE_NO_DMA        no global -> LDS loads (the rings keep whatever they hold)
+//   FQ_ABLATE_NO_MULTIPLY   no wavefront multiplies: loads, waits, barriers and epilogue only
+//   FQ_ABLATE_NO_DEQUANT    the MFMAs and their LDS reads, without the converts and FMAs
+//   FQ_ABLATE_EXTRA_SALU=n  n dependent scalar additions behind every barrier of the k-loop
+//   FQ_ABLATE_ONE_STAGER    wavefronts 0-3 (one per SIMD) issue all loads, 16 each, 4-7 none
 namespace fq {
 
 namespace {
@@ -67,6 +75,9 @@ __device__ inline void stage_half_block(const int8_t* src, int8_t* lds_dst, int 
   const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
   const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
   src = reinterpret_cast<const int8_t*>(((uint64_t)hi << 32) | lo);
+#ifdef FQ_ABLATE_NO_DMA
+  if (voff != 0xFFFFFFFFu) return;
+#endif
   // 4 loads share one base (global and LDS) and differ only in the instruction offset
 #pragma unroll
   for (int b = 0; b < 2; ++b) {
@@ -211,6 +222,7 @@ __device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, 
       pin(st.P[u & 1][q]);
     }
     __builtin_amdgcn_sched_barrier(0);   // MFMA first: its destination must not alias live tiles
+#ifndef FQ_ABLATE_NO_DEQUANT
     {
       // FMAs of the 2 elements converted in the previous slot (unit u-1, or u-2 for n = 0);
       // negative units are the last two units of the previous item
@@ -230,6 +242,7 @@ __device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, 
     st.T[1] = (float)st.P[(u - 1) & 1][n >> 1][2 * (n & 1) + 1];
     pin(st.T[0], st.T[1]);
     __builtin_amdgcn_sched_barrier(0);
+#endif
   }
 }
 
@@ -300,9 +313,16 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
 
   // ---- what this wave stages: 8 KiB (half a block) per item; the first 2*kBI waves the A
   // blocks, the others the B blocks
+#ifdef FQ_ABLATE_ONE_STAGER
+  const bool stager = w < 4;                      // whole blocks: A blocks first, then B blocks
+  const bool stage_a = w < kBI;
+  const int sidx = stage_a ? w : (w - kBI) & 3;
+  const int spart = 0;
+#else
   const bool stage_a = w < 2 * kBI;
   const int sidx = stage_a ? (w >> 1) : ((w - 2 * kBI) >> 1);   // which block of the set
   const int spart = (w & 1) * (kBlockBytes / 2);
+#endif
   int sblk = 0;
 #pragma unroll
   for (int i = 0; i < kBI; ++i) if (stage_a && sidx == i) sblk = ib[i];
@@ -363,6 +383,9 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
   };
   // Stages this wave's 8 KiB share of item (k, res) into ring slot `asel` (A) / k & 1 (B).
   auto stage_item = [&](int k, int res, const KRec<G>& r, int asel, bool new_b) {
+#ifdef FQ_ABLATE_ONE_STAGER
+    if (!stager) return;
+#endif
     if (stage_a) {
       const int8_t* src;
       if (res) {
@@ -375,8 +398,15 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
         src = smain + (int64_t)k * kBlockBytes;
       }
       stage_half_block(src, a_ring + asel * G::kASet + soff, lane);
+#ifdef FQ_ABLATE_ONE_STAGER
+      stage_half_block(src + kBlockBytes / 2, a_ring + asel * G::kASet + soff + kBlockBytes / 2, lane);
+#endif
     } else if (new_b) {
       stage_half_block(smain + (int64_t)k * kBlockBytes, b_ring + (k & 1) * G::kBSet + soff, lane);
+#ifdef FQ_ABLATE_ONE_STAGER
+      stage_half_block(smain + (int64_t)k * kBlockBytes + kBlockBytes / 2,
+                       b_ring + (k & 1) * G::kBSet + soff + kBlockBytes / 2, lane);
+#endif
     }
   };
   // scale column sc belongs to the wave's second j-block?
@@ -453,7 +483,11 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
         }
       if (!res) poison |= my_slot == -2;
       // a residual item is work only for the wavefronts whose i-block is flagged at this k
+#ifdef FQ_ABLATE_NO_MULTIPLY
+      const bool active = p.M < 0;
+#else
       const bool active = !res || my_slot >= 0;
+#endif
       ItemScales<G> sc;
 #pragma unroll
       for (int q = 0; q < G::kSC; ++q)
@@ -470,6 +504,20 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
       // next item and frees this item's ring slots for the item after it.
       __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
       __syncthreads();
+#ifdef FQ_ABLATE_EXTRA_SALU
+      {
+        int chain = k;
+#pragma unroll
+        for (int i = 0; i < FQ_ABLATE_EXTRA_SALU; ++i) asm volatile("s_add_i32 %0, %0, 1" : "+s"(chain));
+        asm volatile("" :: "s"(chain));
+      }
+#endif
+#ifdef FQ_ABLATE_ONE_STAGER
+      if (has2) {
+        if (n2res) stage_item(k + 1, 1, r1, t & 1, false);
+        else stage_item(n2k, 0, r1, t & 1, n2k != n1k);
+      }
+#else
       if (has2) {
         if (stage_a) {
           if (n2res) stage_item(k + 1, 1, r1, t & 1, false);
@@ -478,6 +526,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
           late_b_k = n2k;
         }
       }
+#endif
 
       if (active) {
         run_units_range<G, kUnits - 2, kUnits>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
