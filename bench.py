@@ -179,6 +179,38 @@ def criteria(args):
     return {"workload": wl.name + "_selectors", "rows": M, "cols": K, "blocks": nb, "selectors": rows}
 
 
+def quantizer_sizes(args):
+    """fq_quantize (abs-max threshold, 5 % of the blocks flagged at random, drawn on the device)
+    over activation sizes: time, algorithmic GB/s at (3 + f) B per element, and the fixed cost
+    and streaming rate of the least-squares line time = t0 + bytes / rate through the points."""
+    import torch
+    import paper_2503_08040_amd as fq
+    g = torch.Generator(device="cuda")
+    g.manual_seed(11)
+    rows = []
+    for M, K in ((2048, 4096), (4096, 4096), (8192, 4096), (8192, 8192), (8192, 11008), (16384, 8192)):
+        x = torch.randn((M, K), device="cuda", generator=g, dtype=torch.float32)
+        nbr, nbc = M // 128, K // 128
+        pick = torch.randperm(nbr * nbc, device="cuda", generator=g)[: int(round(0.05 * nbr * nbc))]
+        xb = x.view(nbr, 128, nbc, 128)
+        xb[pick // nbc, 5, pick % nbc, 7] = 200.0          # one outlier per flagged block
+        x = x.to(torch.bfloat16)
+        out = fq.QTensor(M, K)
+        ms = _time_loop(lambda: fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, 20.0, out=out), 0.3, 100)
+        f = fq.fq_qtensor_check(out) / (nbr * nbc)
+        nbytes = (3.0 + f) * M * K
+        rows.append({"rows": M, "cols": K, "flagged_fraction": round(f, 4), "ms": round(ms, 5),
+                     "algorithmic_gbs": round(nbytes / ms / 1e6, 1),
+                     "frac_of_hbm_peak": round(nbytes / ms / 1e6 / HBM_PEAK_GBS, 4)})
+        log(f"[quantizer-sizes] {rows[-1]}")
+        del x, xb, out
+    b = np.array([(3.0 + r["flagged_fraction"]) * r["rows"] * r["cols"] for r in rows])
+    t = np.array([r["ms"] * 1e-3 for r in rows])
+    slope, t0 = np.polyfit(b, t, 1)
+    return {"workload": "fq_quantize over activation sizes, 5 % of the blocks flagged", "sizes": rows,
+            "fit": {"fixed_us": round(t0 * 1e6, 2), "streaming_gbs": round(1.0 / slope / 1e9, 1)}}
+
+
 def sweep(args):
     """Workload config 5 (the square problem): M = K = N = 8192, fallback fraction and placement swept."""
     import torch
@@ -489,6 +521,8 @@ def main():
     ap.add_argument("--pipeline-probe", action="store_true",
                     help="run the register-resident pipeline probe (cycles per unit and clock of the "
                          "MFMA + dequantization mix; about 15 s) and print its table as one JSON object")
+    ap.add_argument("--quantizer-sizes", action="store_true",
+                    help="time fq_quantize over activation sizes: fixed cost and streaming rate")
     ap.add_argument("--gemm-ablation", action="store_true",
                     help="time fq_gemm with each ablation build of the library (a component of the "
                          "k-loop removed or added); prints one JSON object with a table")
@@ -544,6 +578,9 @@ def main():
         return
     if args.group_sweep:
         print(json.dumps(group_sweep(args)), flush=True)
+        return
+    if args.quantizer_sizes:
+        print(json.dumps(quantizer_sizes(args)), flush=True)
         return
     if args.gemm_only:
         print(json.dumps(gemm_only(args)), flush=True)

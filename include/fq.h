@@ -305,9 +305,11 @@ fq_status fq_rmsnorm_forward(const void *x_bf16, const void *w_bf16, int32_t row
  * x~ = a*q, xh = x~ * rstd, g = dy * w,
  *   dx = rstd * (g - xh * mean(g * xh))   [rows, ldo] bf16,
  *   dw[c] = sum over rows of dy * xh      [cols] float.
- * Three kernels: the row means (one workgroup per row), dx together with partial column sums of
- * dy * xh (rows part, part + n_parts, ... per part; 1 <= n_parts <= 65535, 256 is a good choice),
- * and the sum of the parts in a fixed order, so dw is deterministic for a given n_parts.
+ * Up to 16384 columns: one pass over dy and the context (workgroup `part` takes the rows part,
+ * part + n_parts, ... one at a time: row mean, dx and its partial column sums of dy * xh from the
+ * same registers), then the sum of the parts in a fixed order, so dw is deterministic for a given
+ * n_parts.  Wider rows: the row means first (one workgroup per row), then dx and the partial sums
+ * from a second read.  1 <= n_parts <= 65535; one part per compute unit (256) is a good choice.
  * workspace: device, float [n_parts * cols + rows], overwritten.  rows == 0 writes dw = 0.
  */
 fq_status fq_rmsnorm_backward(const void *dy_bf16, int64_t ld_dy, const uint8_t *ctx_packed,

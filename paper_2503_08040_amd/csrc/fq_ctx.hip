@@ -390,6 +390,140 @@ __global__ __launch_bounds__(kCtxThreads) void rmsnorm_dx_dw_kernel(RmsParams p)
     if (q0.c0 + i < p.cols) dst[i] = dwacc[i];
 }
 
+// Backward in one pass for rows of up to 16384 columns: a 512-thread workgroup `part` takes the
+// rows part, part + n_parts, ... one at a time, thread t the 16 values of lane t % 8 of group
+// t / 8 in each half of the row (8192 columns).  The row's dy and context are read once (one row
+// ahead of their use); dy and xh = x~ * rstd stay in registers while the workgroup reduces the row's
+// mean m of g * xh (g = dy * w), then dx = rstd * (g - xh * m) is written and dy * xh is added to
+// the workgroup's column sums, which leave through the same [n_parts, cols] partial sums as in
+// the two-pass form.  Per element: 2 (dy) + 1.28 (context) read, 2 (dx) written instead of twice
+// the reads.
+constexpr int kBwdThreads = 512;
+constexpr int kBwdChunkGroups = kBwdThreads / kLanesPerGroup;      // 64 groups = 8192 columns
+constexpr int kBwdMaxChunks = 2;
+
+// kVec: every matrix of the call allows 16-byte accesses and cols is a multiple of 16, so a live
+// lane always owns 16 whole values: its loads and stores are unconditional vector accesses (dead
+// lanes read a valid address and discard what they get), which keeps the row loop free of the
+// per-access branches of the general form.
+template <int kCh, bool kVec>
+__global__ __launch_bounds__(kBwdThreads, 2) void rmsnorm_backward_row_kernel(RmsParams p) {
+  __shared__ float red[kBwdThreads / 64];
+  const int part = blockIdx.x;
+  const int s = (int)(threadIdx.x % kLanesPerGroup);
+  float wv[kCh][kValsPerLane];      // the gain, unpacked once
+  float dwacc[kCh][kValsPerLane];
+  bool live[kCh];
+  int grp[kCh], c0[kCh];
+#pragma unroll
+  for (int ch = 0; ch < kCh; ++ch) {
+    const int j = ch * kBwdChunkGroups + (int)(threadIdx.x / kLanesPerGroup);
+    grp[ch] = j < p.ng ? j : 0;
+    c0[ch] = grp[ch] * kCtxGroup + s * kValsPerLane;
+    live[ch] = j < p.ng && c0[ch] < p.cols;
+    load16(p.w + c0[ch], live[ch], p.vec_w, c0[ch], p.cols, wv[ch]);
+#pragma unroll
+    for (int i = 0; i < kValsPerLane; ++i) dwacc[ch][i] = 0.0f;
+  }
+  const v4u zero4 = {0u, 0u, 0u, 0u};
+  // the packed dy and context of a row, requested one row ahead of their use
+  v4u dyn[kCh][2];
+  uint32_t cwn[kCh][5];
+  float csn[kCh];
+  auto request = [&](int64_t r) {
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch) {
+      const int64_t g = r * p.ng + grp[ch];
+      const uint32_t* srcw = reinterpret_cast<const uint32_t*>(p.packed + g * kCtxGroupBytes) + s * 5;
+      if (kVec) {
+        const v4u* v = reinterpret_cast<const v4u*>(p.dy + r * p.ld_dy + c0[ch]);
+        dyn[ch][0] = v[0];
+        dyn[ch][1] = v[1];
+#pragma unroll
+        for (int i = 0; i < 5; ++i) cwn[ch][i] = srcw[i];
+        csn[ch] = p.scales[g];
+      } else {
+        load16_raw(p.dy + r * p.ld_dy + c0[ch], live[ch], p.vec_ok, c0[ch], p.cols, dyn[ch]);
+#pragma unroll
+        for (int i = 0; i < 5; ++i) cwn[ch][i] = live[ch] ? srcw[i] : 0u;
+        csn[ch] = live[ch] ? p.scales[g] : 0.0f;
+      }
+    }
+  };
+  if (part < p.rows) request(part);
+  for (int64_t r = part; r < p.rows; r += p.n_parts) {
+    v4u dyr[kCh][2];
+    uint32_t cw[kCh][5];
+    float cs[kCh];
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch) {
+      // (kVec: what a dead lane has read is dropped here)
+      dyr[ch][0] = (kVec && !live[ch]) ? zero4 : dyn[ch][0];
+      dyr[ch][1] = (kVec && !live[ch]) ? zero4 : dyn[ch][1];
+#pragma unroll
+      for (int i = 0; i < 5; ++i) cw[ch][i] = cwn[ch][i];
+      cs[ch] = (kVec && !live[ch]) ? 0.0f : csn[ch];
+    }
+    if (r + p.n_parts < p.rows) request(r + p.n_parts);
+    const float rstd = p.rstd[r];
+    float xh[kCh][kValsPerLane], dyf[kCh][kValsPerLane];
+    float m = 0.0f;
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch) {
+      unpack16(dyr[ch], dyf[ch]);
+#pragma unroll
+      for (int i = 0; i < kValsPerLane; ++i) {
+        const int pos = 10 * i, word = pos >> 5, sh = pos & 31;
+        uint32_t bits = cw[ch][word] >> sh;
+        if (sh > 22) bits |= cw[ch][word + 1] << (32 - sh);
+        const int code = (int)(bits << 22) >> 22;   // sign-extend the 10-bit field
+        xh[ch][i] = (cs[ch] * (float)code) * rstd;
+        m = __builtin_fmaf(dyf[ch][i] * wv[ch][i], xh[ch][i], m);
+      }
+    }
+    // sum over the workgroup, every thread gets the result
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m += __shfl_xor(m, off, 64);
+    __syncthreads();  // red may still be read from the previous row
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = ((red[0] + red[1]) + (red[2] + red[3])) + ((red[4] + red[5]) + (red[6] + red[7]));
+    m = __fdiv_rn(m, (float)p.cols);
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch) {
+      float dx[kValsPerLane];
+#pragma unroll
+      for (int i = 0; i < kValsPerLane; ++i) {
+        dx[i] = rstd * (dyf[ch][i] * wv[ch][i] - xh[ch][i] * m);
+        dwacc[ch][i] = __builtin_fmaf(dyf[ch][i], xh[ch][i], dwacc[ch][i]);
+      }
+      if (kVec) {
+        if (live[ch]) {
+          v4u lo, hi;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            lo[i] = pack_bf16x2(dx[2 * i], dx[2 * i + 1]);
+            hi[i] = pack_bf16x2(dx[8 + 2 * i], dx[8 + 2 * i + 1]);
+          }
+          v4u* o = reinterpret_cast<v4u*>(p.dx + r * p.ldo + c0[ch]);
+          o[0] = lo;
+          o[1] = hi;
+        }
+      } else if (live[ch]) {
+        store16(p.dx + r * p.ldo + c0[ch], p.vec_ok, c0[ch], p.cols, dx);
+      }
+    }
+  }
+#pragma unroll
+  for (int ch = 0; ch < kCh; ++ch) {
+    if (!live[ch]) continue;
+    float* dst = p.dw_parts + (int64_t)part * p.cols + c0[ch];
+#pragma unroll
+    for (int i = 0; i < kValsPerLane; ++i)
+      if (c0[ch] + i < p.cols) dst[i] = dwacc[ch][i];
+  }
+}
+
 // dw[c] = sum of the partial sums, in a fixed order: thread (slice k of 16, column c) adds the
 // parts k, k + 16, k + 32, ... into eight interleaved running sums (eight loads in flight), folds
 // them pairwise, and the sixteen slice sums of a column are folded pairwise in slice order.
@@ -433,7 +567,18 @@ hipError_t launch_rmsnorm(const RmsParams& p, bool backward, hipStream_t st) {
   }
   // no rows: nothing is read (the other pointers may be NULL); summing zero parts writes dw = 0
   const int n_parts = p.rows > 0 ? p.n_parts : 0;
-  if (p.rows > 0) {
+  const int bwd_chunks = (p.ng + kBwdChunkGroups - 1) / kBwdChunkGroups;
+  if (p.rows > 0 && bwd_chunks <= kBwdMaxChunks) {
+    const dim3 grid((unsigned)p.n_parts), block(kBwdThreads);
+    const bool vec = p.vec_ok && p.vec_w && p.cols % kValsPerLane == 0;
+    if (bwd_chunks == 1) {
+      if (vec) hipLaunchKernelGGL((rmsnorm_backward_row_kernel<1, true>), grid, block, 0, st, p);
+      else hipLaunchKernelGGL((rmsnorm_backward_row_kernel<1, false>), grid, block, 0, st, p);
+    } else {
+      if (vec) hipLaunchKernelGGL((rmsnorm_backward_row_kernel<2, true>), grid, block, 0, st, p);
+      else hipLaunchKernelGGL((rmsnorm_backward_row_kernel<2, false>), grid, block, 0, st, p);
+    }
+  } else if (p.rows > 0) {
     hipLaunchKernelGGL(rmsnorm_rowdot_kernel, dim3((unsigned)p.rows), dim3(kCtxThreads), 0, st, p);
     hipLaunchKernelGGL(rmsnorm_dx_dw_kernel, dim3((unsigned)chunks, (unsigned)p.n_parts),
                        dim3(kCtxThreads), 0, st, p);
