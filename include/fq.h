@@ -354,6 +354,22 @@ fq_status fq_gemm(fq_op op, const fq_qtensor *A, const fq_qtensor *B, void *C,
                   fq_out_dtype cdt, int64_t ldc, void *hip_stream);
 
 /*
+ * fq_gemm within a tolerance instead of bit for bit (Sec. 4.5 / Fig. 1b: the dequantization on
+ * the general-purpose ALUs is what limits the INT8 GEMM; this variant halves it).  Same operands,
+ * same order of the terms, block 128 only (FQ_ERR_BLOCK otherwise).  The INT32 block products are
+ * not converted: the matrix instructions accumulate onto the bit pattern of 1.25 * 2^23, the
+ * finished value read as binary32 is exactly 1.25 * 2^23 + P, one fused multiply-add per element
+ * adds (1.25 * 2^23 + P) * s, and 1.25 * 2^23 times the sum of the scales used is subtracted after
+ * every 4 items of the k-loop.  The FP32 additions therefore round at the magnitude of the biased
+ * partial sums: the result differs from fq_gemm's by up to about 2e-4 of max |C| (measured; the
+ * bound does not grow with K), inside the 1e-3 this library's outputs are held to, but it is not
+ * the oracle's result bit for bit.  fq_gemm stays the reference path.  Arguments and errors as
+ * fq_gemm.
+ */
+fq_status fq_gemm_biased(fq_op op, const fq_qtensor *A, const fq_qtensor *B, void *C,
+                         fq_out_dtype cdt, int64_t ldc, void *hip_stream);
+
+/*
  * Eq. (1) (no fallback term: A and B quantized with FQ_CRIT_NONE) on the library's plain
  * kernel: one workgroup per 128 x 128 output tile, per 32 x 32 sub-tile and k-group block/32
  * matrix instructions into an INT32 tile, then one convert and one fused multiply-add per

@@ -26,7 +26,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("FQ_LIBRARY") or os.path.join(_HERE, "libfq.so")
 
 EXPORTS = ["fq_qtensor_bytes", "fq_qtensor_bind", "fq_quantize", "fq_quantize_sr", "fq_quantize_topk",
-           "fq_threshold_update", "fq_gemm", "fq_gemm_plain",
+           "fq_threshold_update", "fq_gemm", "fq_gemm_plain", "fq_gemm_biased",
            "fq_gemm_debug_partials", "fq_codes_to_rowmajor", "fq_qtensor_check",
            "fq_status_string", "fq_ctx_packed_bytes", "fq_ctx_scales_bytes", "fq_ctx_quantize",
            "fq_ctx_dequantize", "fq_gemm_tile_plan", "fq_glu_forward", "fq_glu_backward", "fq_rmsnorm_forward",
@@ -83,6 +83,8 @@ def lib():
                               C.c_int, C.c_int64, C.c_void_p]
         L.fq_gemm_plain.restype = C.c_int
         L.fq_gemm_plain.argtypes = L.fq_gemm.argtypes
+        L.fq_gemm_biased.restype = C.c_int
+        L.fq_gemm_biased.argtypes = L.fq_gemm.argtypes
         L.fq_gemm_debug_partials.restype = C.c_int
         L.fq_gemm_debug_partials.argtypes = [C.c_int, C.POINTER(fq_qtensor), C.POINTER(fq_qtensor),
                                              C.c_int32, C.c_int, C.c_void_p, C.c_void_p]
@@ -264,6 +266,11 @@ def gemm_out_shape(op, A: QTensor, B: QTensor):
 def fq_gemm_plain(op, A: QTensor, B: QTensor, out=None, out_dtype=None, stream=None):
     """Eq. (1) on the plain kernel (any block size, no fallback); see fq.h."""
     return fq_gemm(op, A, B, out, out_dtype, stream, _entry="fq_gemm_plain")
+
+
+def fq_gemm_biased(op, A: QTensor, B: QTensor, out=None, out_dtype=None, stream=None):
+    """fq_gemm within a tolerance (about 2e-4 of max |C|) with half the dequantization work; see fq.h."""
+    return fq_gemm(op, A, B, out, out_dtype, stream, _entry="fq_gemm_biased")
 
 
 def fq_gemm(op, A: QTensor, B: QTensor, out=None, out_dtype=None, stream=None, _entry="fq_gemm"):

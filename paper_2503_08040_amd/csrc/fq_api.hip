@@ -436,13 +436,17 @@ fq_status fq_rmsnorm_backward_static(const void* dy_bf16, int64_t ld_dy, const u
 }
 
 namespace {
+enum GemmKind { kGemmExact, kGemmPlain, kGemmBiased };
 fq_status gemm_impl(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,
-                    int64_t ldc, bool plain, void* hip_stream) {
+                    int64_t ldc, GemmKind kind, void* hip_stream) {
   fq::GemmParams g;
   fq_status s = prepare_gemm(op, A, B, &g);
   if (s != FQ_OK) return s;
   if (cdt != FQ_OUT_F32 && cdt != FQ_OUT_BF16) return FQ_ERR_ENUM;
   if (ldc < g.N) return FQ_ERR_SHAPE;
+  if (kind == kGemmBiased && g.group != FQ_BLOCK) return FQ_ERR_BLOCK;
+  const bool plain = kind == kGemmPlain;
+  g.biased = kind == kGemmBiased ? 1 : 0;
   if (g.M == 0 || g.N == 0) return FQ_OK;
   if (!C) return FQ_ERR_NULL;
   g.c = C; g.ldc = ldc; g.out_bf16 = cdt == FQ_OUT_BF16;
@@ -457,13 +461,18 @@ fq_status gemm_impl(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C,
 
 fq_status fq_gemm(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C, fq_out_dtype cdt,
                   int64_t ldc, void* hip_stream) {
-  return gemm_impl(op, A, B, C, cdt, ldc, false, hip_stream);
+  return gemm_impl(op, A, B, C, cdt, ldc, kGemmExact, hip_stream);
+}
+
+fq_status fq_gemm_biased(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C,
+                         fq_out_dtype cdt, int64_t ldc, void* hip_stream) {
+  return gemm_impl(op, A, B, C, cdt, ldc, kGemmBiased, hip_stream);
 }
 
 fq_status fq_gemm_plain(fq_op op, const fq_qtensor* A, const fq_qtensor* B, void* C,
                         fq_out_dtype cdt, int64_t ldc, void* hip_stream) {
   if (A && A->criterion != FQ_CRIT_NONE) return FQ_ERR_ENUM;    // Eq. (1) only: no fallback term
-  return gemm_impl(op, A, B, C, cdt, ldc, true, hip_stream);
+  return gemm_impl(op, A, B, C, cdt, ldc, kGemmPlain, hip_stream);
 }
 
 fq_status fq_gemm_tile_plan(int32_t rows_out, int32_t cols_out, int32_t compute_units,

@@ -183,10 +183,15 @@ struct ItemScales {
 //   a_cur: A set of the current item in LDS; a_nxt / b_nxt: A set / B set of the next item.
 //   sc: scales of the current item; sp: scales of the previous item's last two units.
 //   h, c: this wavefront's row half and column group.
-template <class G, int u>
+//   kBiased: the tolerance variant (see gemm_biased_kernel): the first MFMA of a quadrant starts
+//   from `magic` (the bit pattern of 1.25 * 2^23 in every element) instead of zero, so that the
+//   finished INT32 value, read as binary32, IS 1.25 * 2^23 + P, exactly; the slot then issues only
+//   the 2 FMAs of elements 2n, 2n+1 of unit u-1 straight from that tile and no converts.
+template <class G, int u, bool kBiased>
 __device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, const int8_t* a_nxt,
                                          const int8_t* b_nxt, int h, int c, int lane,
-                                         const ItemScales<G>& sc, const float (&sp)[G::kSP]) {
+                                         const ItemScales<G>& sc, const float (&sp)[G::kSP],
+                                         const v4i& magic) {
   constexpr int kSJ = G::kSJ, kUnits = G::kUnits;
   constexpr int si = u / kSJ, sj = u % kSJ;
   // B operand (ch, ks) of column group cg = kSJ*c + j of the tile: block cg / 4, group cg % 4
@@ -200,7 +205,7 @@ __device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, 
     {
       const v4i z = {0, 0, 0, 0};
       st.P[u & 1][q] = __builtin_amdgcn_mfma_i32_16x16x64_i8(
-          st.aq[si & 1][rh][ks], st.bq[sj][ch][ks], ks ? st.P[u & 1][q] : z, 0, 0, 0);
+          st.aq[si & 1][rh][ks], st.bq[sj][ch][ks], ks ? st.P[u & 1][q] : (kBiased ? magic : z), 0, 0, 0);
       // B operand (ch, ks) was used for the last time in the slot with rh = 1
       const bool b_done = rh == 1;
       // the other four slots (rh = 0) carry a load each into a free buffer: operand i = 0..3
@@ -223,7 +228,21 @@ __device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, 
     }
     __builtin_amdgcn_sched_barrier(0);   // MFMA first: its destination must not alias live tiles
 #ifndef FQ_ABLATE_NO_DEQUANT
-    {
+    if constexpr (kBiased) {
+      constexpr int kLastSi = G::kSI - 1;
+      constexpr int fu = u - 1;
+      constexpr bool prev = fu < 0;                     // the last unit of the previous item
+      constexpr int pu = fu + kUnits;
+      constexpr int fsi = prev ? kLastSi : fu / kSJ, fsj = prev ? pu % kSJ : fu % kSJ;
+      const float s = prev ? sp[G::kSP - 1] : sc.s[G::kSC == 1 ? 0 : fsj];
+      const int fe = 2 * n;
+      st.acc[fsi][fsj][fe] = __builtin_fmaf(
+          __int_as_float(st.P[(u - 1) & 1][n >> 1][2 * (n & 1)]), s, st.acc[fsi][fsj][fe]);
+      st.acc[fsi][fsj][fe + 1] = __builtin_fmaf(
+          __int_as_float(st.P[(u - 1) & 1][n >> 1][2 * (n & 1) + 1]), s, st.acc[fsi][fsj][fe + 1]);
+      pin(st.acc[fsi][fsj][fe], st.acc[fsi][fsj][fe + 1]);
+      __builtin_amdgcn_sched_barrier(0);
+    } else {
       // FMAs of the 2 elements converted in the previous slot (unit u-1, or u-2 for n = 0);
       // negative units are the last two units of the previous item
       constexpr int kLastSi = G::kSI - 1;
@@ -237,31 +256,41 @@ __device__ __forceinline__ void run_unit(WaveState<G>& st, const int8_t* a_cur, 
       st.acc[fsi][fsj][fe + 1] = __builtin_fmaf(st.T[1], s, st.acc[fsi][fsj][fe + 1]);
       pin(st.acc[fsi][fsj][fe], st.acc[fsi][fsj][fe + 1]);
     }
-    __builtin_amdgcn_sched_barrier(0);   // FMAs before converts
-    st.T[0] = (float)st.P[(u - 1) & 1][n >> 1][2 * (n & 1)];
-    st.T[1] = (float)st.P[(u - 1) & 1][n >> 1][2 * (n & 1) + 1];
-    pin(st.T[0], st.T[1]);
-    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (!kBiased) {
+      __builtin_amdgcn_sched_barrier(0);   // FMAs before converts
+      st.T[0] = (float)st.P[(u - 1) & 1][n >> 1][2 * (n & 1)];
+      st.T[1] = (float)st.P[(u - 1) & 1][n >> 1][2 * (n & 1) + 1];
+      pin(st.T[0], st.T[1]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
 #endif
   }
 }
 
 // Units [kFrom, kTo) of one item, in order.
-template <class G, int kFrom, int kTo>
+template <class G, int kFrom, int kTo, bool kBiased>
 __device__ __forceinline__ void run_units_range(WaveState<G>& st, const int8_t* a_cur,
                                                 const int8_t* a_nxt, const int8_t* b_nxt, int h,
                                                 int c, int lane, const ItemScales<G>& sc,
-                                                const float (&sp)[G::kSP]) {
+                                                const float (&sp)[G::kSP], const v4i& magic) {
   if constexpr (kFrom < kTo) {
-    run_unit<G, kFrom>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
-    run_units_range<G, kFrom + 1, kTo>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
+    run_unit<G, kFrom, kBiased>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp, magic);
+    run_units_range<G, kFrom + 1, kTo, kBiased>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp, magic);
   }
 }
 
 // Folds the last two units of the last item (scales sp) into the accumulators.
-template <class G>
+template <class G, bool kBiased>
 __device__ __forceinline__ void drain(WaveState<G>& st, const float (&sp)[G::kSP]) {
   constexpr int kLastSi = G::kSI - 1, kSJ = G::kSJ, kP = (G::kUnits - 1) & 1;
+  if constexpr (kBiased) {      // only the last unit is pending: all 16 elements of its biased tile
+    const float s = sp[G::kSP - 1];
+#pragma unroll
+    for (int e = 0; e < 16; ++e)
+      st.acc[kLastSi][kSJ - 1][e] =
+          __builtin_fmaf(__int_as_float(st.P[kP][e >> 2][e & 3]), s, st.acc[kLastSi][kSJ - 1][e]);
+    return;
+  }
 #pragma unroll
   for (int n = 0; n < 8; ++n) {
     const int fsj = n ? kSJ - 1 : kSJ - 2, fe = n ? 2 * (n - 1) : 14;
@@ -292,7 +321,17 @@ namespace {
 
 // One output tile of geometry G whose first blocks are (ib_first, jb_first).  Blocks beyond
 // the matrix repeat the last valid one (their products are never stored).
-template <class G>
+// kBiased: the tolerance variant.  Every item adds (1.25 * 2^23 + P) * s instead of P * s to the
+// accumulators; the wavefront keeps the sum of the scales it has used per scale column and,
+// after every kBiasWindow items it took part in (and at the end), folds the pending unit and
+// subtracts 1.25 * 2^23 times that sum with one FMA per accumulator.  The window bounds the
+// magnitude the accumulators carry, and with it the rounding error of the additions, whatever K.
+constexpr int kBiasWindow = 4;
+constexpr int kMagicBits = 0x4B200000;          // 1.25 * 2^23 as binary32: with |P| <= 128 * 127^2 < 2^21 the sum
+                                                // stays inside [2^23, 2^24), where one ulp is 1
+constexpr float kMagic = 10485760.0f;
+
+template <class G, bool kBiased>
 __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int jb_first,
                                           int8_t* lds) {
   constexpr int kBI = G::kBI, kBJ = G::kBJ, kSI = G::kSI, kSJ = G::kSJ, kUnits = G::kUnits;
@@ -420,6 +459,25 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
 #pragma unroll
       for (int r = 0; r < 16; ++r) st.acc[si][sj][r] = 0.0f;
   bool poison = false;           // this wavefront's i-block has a flagged block without a slot
+  v4i magic = {kMagicBits, kMagicBits, kMagicBits, kMagicBits};
+  if (kBiased) asm volatile("" : "+v"(magic));   // stays in registers: an MFMA operand cannot be a literal
+  float bias_s[G::kSC];          // kBiased: sum of the scales used since the bias was last removed
+#pragma unroll
+  for (int q = 0; q < G::kSC; ++q) bias_s[q] = 0.0f;
+  int bias_items = 0;
+  // removes the bias accumulated so far; the pipeline must have been drained
+  auto remove_bias = [&]() {
+#pragma unroll
+    for (int si = 0; si < kSI; ++si)
+#pragma unroll
+      for (int sj = 0; sj < kSJ; ++sj)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          st.acc[si][sj][e] = __builtin_fmaf(bias_s[G::kSC == 1 ? 0 : sj], -kMagic, st.acc[si][sj][e]);
+#pragma unroll
+    for (int q = 0; q < G::kSC; ++q) bias_s[q] = 0.0f;
+    bias_items = 0;
+  };
 
   if (nkb > 0) {
     // ---- prologue: items 0 and 1 into the two ring slots
@@ -497,7 +555,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
       const int8_t* const a_nxt = a_ring + ((t + 1) & 1) * G::kASet;
       const int8_t* const b_nxt = b_ring + (n1k & 1) * G::kBSet;
 
-      if (active) run_units_range<G, 0, kUnits - 2>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
+      if (active) run_units_range<G, 0, kUnits - 2, kBiased>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp, magic);
 
       // All LDS reads of this item are issued (the last two units run from registers).  Wait
       // for them and for the next item's direct-to-LDS loads, then the barrier publishes the
@@ -529,9 +587,21 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
 #endif
 
       if (active) {
-        run_units_range<G, kUnits - 2, kUnits>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp);
+        run_units_range<G, kUnits - 2, kUnits, kBiased>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp, magic);
 #pragma unroll
         for (int i = 0; i < G::kSP; ++i) sp[i] = sc.s[G::kSC == 1 ? 0 : kSJ - 2 + i];
+        if constexpr (kBiased) {
+#pragma unroll
+          for (int q = 0; q < G::kSC; ++q) bias_s[q] += sc.s[q];
+          if (++bias_items == kBiasWindow) {
+            // fold the pending unit, take the bias out, and restart the pipeline: the next unit 0
+            // folds the same tile again with scale 0, which adds nothing
+            drain<G, true>(st, sp);
+            remove_bias();
+#pragma unroll
+            for (int i = 0; i < G::kSP; ++i) sp[i] = 0.0f;
+          }
+        }
       } else {
         // nothing to multiply in this item: the pipeline state (the pending tile of the last
         // active item and its scale) stays as it is; only fetch the next item's first operands,
@@ -562,7 +632,8 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
         r2 = load_rec(k + 2);
       }
     }
-    drain<G>(st, sp);
+    drain<G, kBiased>(st, sp);
+    if constexpr (kBiased) remove_bias();
   }
 
   // ---- epilogue.  The MFMA result layout (lane = column, registers = rows) would give 32-byte
@@ -661,10 +732,30 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmParams p) {
   int ti, tj;
   if ((int)blockIdx.x < p.n_main) {
     tile_of(blockIdx.x, (p.nib + 1) >> 1, p.main_tj, ti, tj);
-    tile_body<Geo<2, 2>>(p, 2 * ti, 2 * tj, lds);
+    tile_body<Geo<2, 2>, false>(p, 2 * ti, 2 * tj, lds);
   } else {
     tile_of(blockIdx.x - p.n_main, p.nib, p.tail_tj, ti, tj);
-    tile_body<Geo<1, 3>>(p, ti, 2 * p.main_tj + 3 * tj, lds);
+    tile_body<Geo<1, 3>, false>(p, ti, 2 * p.main_tj + 3 * tj, lds);
+  }
+}
+
+// The tolerance variant of gemm_kernel: same tiles, same k-loop, same order of the terms, but the
+// INT32 block products are folded into the FP32 accumulators without being converted: the first
+// MFMA of every 16 x 16 quadrant accumulates onto the bit pattern of 1.25 * 2^23, so that the
+// finished INT32 value read as binary32 is exactly 1.25 * 2^23 + P (|P| <= 128 * 127^2 < 2^21), one
+// FMA per element adds (1.25 * 2^23 + P) * s, and the bias 1.25 * 2^23 * (sum of the scales used) is
+// taken out every kBiasWindow items.  Half the vector-ALU instructions of Eq. (1) (the two left per
+// MFMA are the ones its issue leaves free); the additions round at the magnitude of the biased
+// sums, so results differ from gemm_kernel's by up to about 2e-4 of max |C|, whatever K.
+__global__ __launch_bounds__(kThreads, 2) void gemm_biased_kernel(GemmParams p) {
+  extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
+  int ti, tj;
+  if ((int)blockIdx.x < p.n_main) {
+    tile_of(blockIdx.x, (p.nib + 1) >> 1, p.main_tj, ti, tj);
+    tile_body<Geo<2, 2>, true>(p, 2 * ti, 2 * tj, lds);
+  } else {
+    tile_of(blockIdx.x - p.n_main, p.nib, p.tail_tj, ti, tj);
+    tile_body<Geo<1, 3>, true>(p, ti, 2 * p.main_tj + 3 * tj, lds);
   }
 }
 
@@ -784,10 +875,14 @@ hipError_t launch_gemm(const GemmParams& p_in, bool debug, hipStream_t st) {
   if (!attr_set[dev].load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_biased_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     attr_set[dev].store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL(gemm_kernel, dim3(grid), dim3(kThreads), kLdsBytes, st, p);
+  if (p.biased) hipLaunchKernelGGL(gemm_biased_kernel, dim3(grid), dim3(kThreads), kLdsBytes, st, p);
+  else hipLaunchKernelGGL(gemm_kernel, dim3(grid), dim3(kThreads), kLdsBytes, st, p);
   return hipGetLastError();
 }
 

@@ -58,6 +58,7 @@ struct GemmParams {
   int n_main, main_tj, tail_tj;   // tile plan, filled in by launch_gemm
   int group;                  // quantization group edge (128, 64, 32)
   int a_ni, a_nk, b_nj;       // extents of the scale grids along i, k (A) and j (B), in groups
+  int biased;                 // tolerance variant: biased INT32 accumulation (gemm_biased_kernel)
   int debug_k;                // debug mode: the single k-block (k-group) to evaluate
   int debug_residual;         // debug mode: 0 main term, 1 residual term
 };
