@@ -361,15 +361,16 @@ def gemm_ablation(args):
     import subprocess
     from paper_2503_08040_amd import build as hip_build
     rows = []
-    for name in ["library"] + list(hip_build.ABLATIONS):
+    for name in ["library", "library_biased"] + list(hip_build.ABLATIONS):
         env = dict(os.environ)
-        if name != "library":
+        if not name.startswith("library"):
             path = hip_build.ablation_lib(name)
             if not os.path.exists(path):
                 raise SystemExit(f"{path} is missing: python -m paper_2503_08040_amd.build")
             env["FQ_LIBRARY"] = path
         r = subprocess.run([sys.executable, os.path.abspath(__file__), "--gemm-only",
-                            "--workload", args.workload, "--steps", str(args.steps)],
+                            "--workload", args.workload, "--steps", str(args.steps)] +
+                           (["--biased"] if name == "library_biased" else []),
                            capture_output=True, text=True, env=env, timeout=600)
         if r.returncode != 0:
             raise SystemExit(f"ablation {name} failed: {r.stderr[-2000:]}")
@@ -393,7 +394,8 @@ def gemm_only(args):
     qx = fq.fq_quantize(x, fq.FQ_CRIT_ABSMAX_GT, wl.theta)
     qw = fq.fq_quantize(w, fq.FQ_CRIT_NONE, 0.0, capacity=0)
     y = torch.empty((wl.M, wl.N), dtype=torch.bfloat16, device="cuda")
-    ms = _time_loop(lambda: fq.fq_gemm(fq.FQ_OP_NT, qx, qw, out=y), 1.0, max(args.steps, 50))
+    entry = fq.fq_gemm_biased if args.biased else fq.fq_gemm
+    ms = _time_loop(lambda: entry(fq.FQ_OP_NT, qx, qw, out=y), 1.0, max(args.steps, 50))
     ops = 2.0 * wl.M * wl.N * wl.K
     return {"ms_gemm": round(ms, 4), "tops": round(ops / ms / 1e9, 1)}
 
@@ -530,6 +532,8 @@ def main():
                          "k-loop removed or added); prints one JSON object with a table")
     ap.add_argument("--gemm-only", action="store_true",
                     help="time fq_gemm alone on the workload and print {ms_gemm, tops}")
+    ap.add_argument("--biased", action="store_true",
+                    help="with --gemm-only: time fq_gemm_biased, the tolerance variant, instead")
     ap.add_argument("--group-sweep", action="store_true",
                     help="Fig. 1b: plain block-INT8 GEMM at group sizes 32, 64, 128 on square problems")
     ap.add_argument("--no-mfma-ceiling", action="store_true",

@@ -267,6 +267,8 @@ void quantize_kernel(QuantParams p) {
 
   // The abs-max decision is known now: take the residual slot right away, so that the round
   // trip of the atomic is hidden behind the quantization of the block.          (Sec. 4.4)
+  // a tensor without residual slots has no list to write (nothing can fall back into it)
+  const bool want_list = p.capacity > 0;
   bool u = false;
   int slot_early = -1;
   unsigned long long group_before = 0;   // thread 0: the group's word before this block's bits
@@ -275,7 +277,7 @@ void quantize_kernel(QuantParams p) {
     u = p.crit == 2 || (p.crit == 1 && amax > p.theta) || (p.crit == 5 && p.mask[blk] != 0);
     if (t == 0) {
       if (u) slot_early = atomicAdd(p.fb_count, 1);
-      group_before = atomicOr(p.fb_words + (blk >> 5), my_bits(blk, u));
+      if (want_list) group_before = atomicOr(p.fb_words + (blk >> 5), my_bits(blk, u));
     }
   }
 
@@ -324,11 +326,10 @@ void quantize_kernel(QuantParams p) {
     }
   }
 
-  // ---- per-block outputs; the workgroup that completes the last group of 32 blocks writes
-  // the list of flagged blocks.  Runs before the block's codes are stored (the two atomics
-  // issued after the decision have had the whole quantization to come back, and no store is
-  // pending that the wait for them would have to sit out); with an error-based criterion
-  // the decision is only known after the codes, so it runs there.
+  // ---- per-block outputs.  Runs before the block's codes are stored (the atomics issued
+  // after the decision have had the whole quantization to come back, and no store is pending
+  // that the wait for them would have to sit out); with an error-based criterion the decision
+  // is only known after the codes, so it runs there.
   int slot = -1;
   auto record_block = [&]() {
     if (t == 0) {
@@ -338,6 +339,16 @@ void quantize_kernel(QuantParams p) {
       p.fb_slot[blk] = slot0;
       if (blk == 0) *p.fb_count_next = 0;   // ready for the next call into this tensor
       slot_sh = slot0;
+    }
+    __syncthreads();
+    slot = slot_sh;
+  };
+  // ---- the list of flagged blocks: the workgroup whose decision completed a group of 32 counts
+  // the group, the one that counts the last group writes the list.  Runs when the workgroup has
+  // issued all its stores, so that nobody's codes wait for the round trip of the counter.
+  auto finish_list = [&]() {
+    if (!want_list) return;       // uniform over the grid
+    if (t == 0) {
       const int nb = (int)gridDim.x, g = blk >> 5;
       const uint32_t full = (nb - 32 * g >= 32) ? 0xFFFFFFFFu : ((1u << (nb - 32 * g)) - 1u);
       const uint32_t decided = (uint32_t)group_before | (1u << (blk & 31));
@@ -346,7 +357,6 @@ void quantize_kernel(QuantParams p) {
       last_sh = last;
     }
     __syncthreads();
-    slot = slot_sh;
     if (last_sh) {      // uniform over the workgroup
       write_fb_list(p.fb_words, (int)gridDim.x, p.capacity, p.fb_list, scan_sh, &scan_base_sh);
       if (t == 0) *p.fb_groups_done = 0;    // ready for the next call
@@ -384,12 +394,15 @@ void quantize_kernel(QuantParams p) {
     else u = l1x > 0.0 && l1 / l1x > (double)p.theta;
     if (t == 0) {
       if (u) slot_early = atomicAdd(p.fb_count, 1);
-      group_before = atomicOr(p.fb_words + (blk >> 5), my_bits(blk, u));
+      if (want_list) group_before = atomicOr(p.fb_words + (blk >> 5), my_bits(blk, u));
     }
   }
 
   if (kErr) record_block();
-  if (slot < 0) return;  // uniform over the workgroup
+  if (slot < 0) {        // uniform over the workgroup
+    finish_list();
+    return;
+  }
 
   // ---- step 2: quantize the residual G - a*codes                 (Sec. 4.3)
   // (the residual is recomputed where it is needed instead of being kept in 64 registers)
@@ -419,6 +432,7 @@ void quantize_kernel(QuantParams p) {
     *reinterpret_cast<v4i*>(rdst + tile_offset(pz * 32 + rp, cc * 16)) = rq[pz];
   if (kWantT) store_transposed(rq, rp, cc, img, p.res_codes_t + (int64_t)slot * kBlockBytes);
   if (t == 0) p.res_scales[slot] = ra;
+  finish_list();
 }
 
 // ---- TopK AbsMax selection (Sec. 4.4), in three launches: the abs-max of every block, the
