@@ -22,8 +22,23 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 def test_help_lists_the_modes():
     r = _run("--help")
     assert r.returncode == 0
-    for flag in ("--steps", "--warmup", "--gpus", "--sweep", "--backward", "--context", "--criteria"):
+    for flag in ("--steps", "--warmup", "--gpus", "--sweep", "--backward", "--context", "--criteria",
+                 "--group-sweep", "--quantizer-sizes", "--pipeline-probe", "--gemm-ablation",
+                 "--gemm-only", "--no-tolerance-variant", "--no-overhead-curve"):
         assert flag in r.stdout
+
+
+def test_ablation_builds_are_declared_with_their_switches():
+    """Every ablation build names a switch that the GEMM source really has."""
+    sys.path.insert(0, ROOT)
+    from paper_2503_08040_amd import build
+    src = open(os.path.join(ROOT, "paper_2503_08040_amd", "csrc", "fq_gemm.hip")).read()
+    assert build.ABLATIONS
+    for name, flags in build.ABLATIONS.items():
+        for f in flags:
+            macro = f[2:].split("=")[0]
+            assert f.startswith("-DFQ_ABLATE_") and macro in src, (name, f)
+        assert build.ablation_lib(name).endswith(f"libfq_ablate_{name}.so")
 
 
 def test_default_workload_is_the_config_the_metric_is_quoted_on():
