@@ -274,6 +274,67 @@ __global__ __launch_bounds__(kThreads, 1) void probe32(const v4i* in, float* out
 }
 
 
+// The 16-bit alternative of Sec. 4.3 for a flagged block: its 32 x 32 x 128 step in bf16 on the
+// matrix cores, 8 v_mfma_f32_32x32x16_bf16 straight into FP32 accumulators.  CONV: 1 = the B
+// operand is made from INT8 codes on the way (per MFMA and lane 8 codes: sign-extend, convert,
+// scale, pack: 28 vector instructions), which is what keeping the weights in INT8 would need;
+// 0 = both operands are bf16 on chip already (twice the operand bytes of the INT8 residual).
+typedef float v16f __attribute__((ext_vector_type(16)));
+template <int CONV, int kThreads>
+__global__ __launch_bounds__(kThreads, 1) void probe_bf16(const v4i* in, float* out, uint64_t* stamps, float s, int trips,
+                                                          const int8_t* /*window*/, int /*far_every*/) {
+  v4i a[4], b[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    // bf16 bit patterns with small magnitudes: sign, exponent 120..127, mantissa from the input
+    const v4i r0 = in[i * 512 + (threadIdx.x & 511)], r1 = in[(4 + i) * 512 + (threadIdx.x & 511)];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      a[i][c] = (r0[c] & 0x807F807F) | 0x3C003C00 | ((r0[c] >> 4) & 0x03800380);
+      b[i][c] = (r1[c] & 0x807F807F) | 0x3C003C00 | ((r1[c] >> 4) & 0x03800380);
+    }
+  }
+  v16f acc[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) acc[u] = v16f{0};
+  float sv = s;
+  asm volatile("" : "+v"(sv));
+  const uint64_t t0 = memtime_now(), r0 = realtime_now();
+  for (int it = 0; it < trips; ++it) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int g = 0; g < 8; ++g) {
+        v4i bb = b[(u + g) & 3];
+        if (CONV) {
+          // 8 INT8 codes (two dwords of the fragment) -> 8 scaled bf16 values (four dwords)
+          const v4i src = b[(u + g) & 3];
+          float f[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            int c8;
+            asm volatile("v_bfe_i32 %0, %1, %2, 8" : "=v"(c8) : "v"(src[e >> 2]), "n"(8 * (e & 3)));
+            asm volatile("v_cvt_f32_i32 %0, %1" : "=v"(f[e]) : "v"(c8));
+            asm volatile("v_mul_f32 %0, %0, %1" : "+v"(f[e]) : "v"(sv));
+          }
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(bb[e]) : "v"(f[2 * e]), "v"(f[2 * e + 1]));
+        }
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(acc[u]) : "v"(a[g & 3]), "v"(bb));
+      }
+  }
+  const uint64_t t1 = memtime_now(), r1 = realtime_now();
+  float r = 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r += acc[u][i];
+  out[blockIdx.x * blockDim.x + threadIdx.x] = r;
+  if (threadIdx.x == 0) { stamps[4 * blockIdx.x] = t1 - t0; stamps[4 * blockIdx.x + 1] = r1 - r0; }
+}
+
+
 static int g_cus;
 static v4i* g_in; static float* g_out; static uint64_t* g_stamps; static int8_t* g_window;
 
@@ -363,5 +424,7 @@ int main() {
   time_kernel(probe32<8, 1, 512, 3, 3, 1>, 512, 4, "mfma32_4fma_4cvt_3reads_dma_early_barrier", "barrier every 8 units + the 8 loads over the first 6 units");
   time_kernel(probe32<8, 1, 512, 3, 1, 0>, 512, 4, "mfma32_4fma_4cvt_3reads_dma_spread", "one direct-to-LDS load per unit, no barrier");
   time_kernel(probe32<8, 1, 512, 3, 2, 1>, 512, 4, "mfma32_4fma_4cvt_3reads_dma_burst_barrier", "barrier every 8 units + the 8 direct-to-LDS loads right behind it");
+  time_kernel(probe_bf16<0, 512>, 512, 4, "bf16_fallback_step", "the 16-bit alternative for a flagged block: 8 MFMA 32x32x16 bf16 per unit, both operands bf16 on chip");
+  time_kernel(probe_bf16<1, 512>, 512, 4, "bf16_fallback_step_b_from_int8", "the same with the B operand converted from INT8 codes on the way (28 vector instructions per MFMA)");
   return 0;
 }
