@@ -306,10 +306,13 @@ fq_status fq_rmsnorm_forward(const void *x_bf16, const void *w_bf16, int32_t row
  *   dx = rstd * (g - xh * mean(g * xh))   [rows, ldo] bf16,
  *   dw[c] = sum over rows of dy * xh      [cols] float.
  * Up to 16384 columns: one pass over dy and the context (workgroup `part` takes the rows part,
- * part + n_parts, ... one at a time: row mean, dx and its partial column sums of dy * xh from the
- * same registers), then the sum of the parts in a fixed order, so dw is deterministic for a given
- * n_parts.  Wider rows: the row means first (one workgroup per row), then dx and the partial sums
- * from a second read.  1 <= n_parts <= 65535; one part per compute unit (256) is a good choice.
+ * part + n_parts, ... : row mean, dx and its partial column sums of dy * xh from one read of
+ * the row), then the sum of the parts in a fixed order, so dw is deterministic for a given
+ * n_parts and dx does not depend on it.  Fastest when every pointer and pitch allows 16-byte
+ * accesses, cols is a multiple of 16 and at most 12288: then two rows are in flight per
+ * workgroup.  Wider rows: the row means first (one workgroup per row), then dx and the partial
+ * sums from a second read.  1 <= n_parts <= 65535; one part per compute unit (256) is a good
+ * choice.
  * workspace: device, float [n_parts * cols + rows], overwritten.  rows == 0 writes dw = 0.
  */
 fq_status fq_rmsnorm_backward(const void *dy_bf16, int64_t ld_dy, const uint8_t *ctx_packed,

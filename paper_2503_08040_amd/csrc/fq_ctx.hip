@@ -390,7 +390,9 @@ __global__ __launch_bounds__(kCtxThreads) void rmsnorm_dx_dw_kernel(RmsParams p)
     if (q0.c0 + i < p.cols) dst[i] = dwacc[i];
 }
 
-// Backward in one pass for rows of up to 16384 columns: a 512-thread workgroup `part` takes the
+// Backward in one pass for rows of up to 16384 columns (rows that the two-team kernel further
+// down does not take: unaligned ones, and 16-byte rows wider than 12288 columns): a 512-thread
+// workgroup `part` takes the
 // rows part, part + n_parts, ... one at a time, thread t the 16 values of lane t % 8 of group
 // t / 8 in each half of the row (8192 columns).  The row's dy and context are read once (one row
 // ahead of their use); dy and xh = x~ * rstd stay in registers while the workgroup reduces the row's
@@ -418,9 +420,10 @@ __global__ __launch_bounds__(kBwdThreads, 2) void rmsnorm_backward_row_kernel(Rm
 #pragma unroll
   for (int ch = 0; ch < kCh; ++ch) {
     const int j = ch * kBwdChunkGroups + (int)(threadIdx.x / kLanesPerGroup);
-    grp[ch] = j < p.ng ? j : 0;
-    c0[ch] = grp[ch] * kCtxGroup + s * kValsPerLane;
-    live[ch] = j < p.ng && c0[ch] < p.cols;
+    const int c = j * kCtxGroup + s * kValsPerLane;
+    live[ch] = j < p.ng && c < p.cols;
+    grp[ch] = live[ch] ? j : 0;     // a dead lane reads the row's first values and drops them
+    c0[ch] = live[ch] ? c : 0;
     load16(p.w + c0[ch], live[ch], p.vec_w, c0[ch], p.cols, wv[ch]);
 #pragma unroll
     for (int i = 0; i < kValsPerLane; ++i) dwacc[ch][i] = 0.0f;
@@ -429,8 +432,9 @@ __global__ __launch_bounds__(kBwdThreads, 2) void rmsnorm_backward_row_kernel(Rm
   // the packed dy and context of a row, requested one row ahead of their use
   v4u dyn[kCh][2];
   uint32_t cwn[kCh][5];
-  float csn[kCh];
+  float csn[kCh], rstdn = 0.0f;
   auto request = [&](int64_t r) {
+    rstdn = p.rstd[r];      // first: the loads return in order, and this one is needed first
 #pragma unroll
     for (int ch = 0; ch < kCh; ++ch) {
       const int64_t g = r * p.ng + grp[ch];
@@ -464,8 +468,8 @@ __global__ __launch_bounds__(kBwdThreads, 2) void rmsnorm_backward_row_kernel(Rm
       for (int i = 0; i < 5; ++i) cw[ch][i] = cwn[ch][i];
       cs[ch] = (kVec && !live[ch]) ? 0.0f : csn[ch];
     }
+    const float rstd = rstdn;
     if (r + p.n_parts < p.rows) request(r + p.n_parts);
-    const float rstd = p.rstd[r];
     float xh[kCh][kValsPerLane], dyf[kCh][kValsPerLane];
     float m = 0.0f;
 #pragma unroll
@@ -524,6 +528,207 @@ __global__ __launch_bounds__(kBwdThreads, 2) void rmsnorm_backward_row_kernel(Rm
   }
 }
 
+// Backward in one pass for 16-byte rows of up to 12288 columns, the form the tall activations
+// of Sec. 5 take.  A team of 256 threads takes one row at a time, thread t the 16 values of lane
+// t % 8 of group t / 8 in each 4096-column chunk.  It keeps the row's dy and context as loaded
+// (packed bf16 pairs, 10-bit fields) and decodes them twice, before and after the row's
+// reduction, instead of holding decoded floats across it: half the registers per value, so a
+// second row's loads fit beside the first.
+constexpr int kTeamThreads = 256;
+constexpr int kTeamGroups = kTeamThreads / kLanesPerGroup;           // 32 groups = 4096 columns
+constexpr int kTeamMaxChunks = 3;
+
+// sum over the wavefront's 64 lanes, every lane gets it: four steps inside a row of 16 lanes by
+// data-parallel-primitive moves, two across rows through the LDS crossbar
+__device__ inline float wave_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));   // lane ^ 1
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));   // lane ^ 2
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, true));  // 7 - lane (of 8)
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, true));  // 15 - lane
+  v += __shfl_xor(v, 16, 64);
+  v += __shfl_xor(v, 32, 64);
+  return v;
+}
+
+// Two such teams form a workgroup, half a row apart: in every step one team decodes a
+// row and reduces it while the other finishes the row it reduced in the step before, with one
+// barrier per step; at the end the second team's column sums are added to the first team's through
+// LDS, so a compute unit writes one set of partial sums and not two.  A team's rows alternate
+// between two register buffers: a row's dy and context are requested into the free buffer while the
+// row before it is reduced, two steps ahead of their use.
+template <int kCh>
+struct PairState {
+  float dwacc[kCh][kValsPerLane];
+  bool live[kCh];
+  int grp[kCh], c0[kCh];
+  v4u dy[2][kCh][2];
+  uint32_t cw[2][kCh][5];
+  float cs[2][kCh], rstd[2];
+};
+
+template <int kCh, int kTeam>
+__device__ __forceinline__ void pair_team_rows(const RmsParams& p, PairState<kCh>& st, float* red,
+                                               const v4u* wl, int part, int t, int s) {
+  auto request = [&](int b, int64_t r) {
+    st.rstd[b] = p.rstd[r];      // first: the loads return in order, and this one is needed first
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch) {
+      const int64_t g = r * p.ng + st.grp[ch];
+      const uint32_t* srcw = reinterpret_cast<const uint32_t*>(p.packed + g * kCtxGroupBytes) + s * 5;
+      const v4u* v = reinterpret_cast<const v4u*>(p.dy + r * p.ld_dy + st.c0[ch]);
+      st.dy[b][ch][0] = v[0];
+      st.dy[b][ch][1] = v[1];
+#pragma unroll
+      for (int i = 0; i < 5; ++i) st.cw[b][ch][i] = srcw[i];
+      st.cs[b][ch] = p.scales[g];
+    }
+  };
+  // element i of chunk ch in buffer b: dy, w and xh = (scale * code) * rstd
+  auto decode = [&](int b, int ch, int i, const v4u (&wv)[2], float& dyf, float& wf, float& xh) {
+    const uint32_t dw = st.dy[b][ch][i >> 3][(i >> 1) & 3], ww = wv[i >> 3][(i >> 1) & 3];
+    dyf = __uint_as_float((i & 1) ? (dw & 0xFFFF0000u) : (dw << 16));
+    wf = __uint_as_float((i & 1) ? (ww & 0xFFFF0000u) : (ww << 16));
+    const int pos = 10 * i, word = pos >> 5, sh = pos & 31;
+    uint32_t bits = st.cw[b][ch][word] >> sh;
+    if (sh > 22) bits |= st.cw[b][ch][word + 1] << (32 - sh);
+    const int code = (int)(bits << 22) >> 22;
+    xh = (st.cs[b][ch] * (float)code) * st.rstd[b];
+  };
+  // one row of this team in buffer b: first half, barrier, second half, barrier
+  auto row = [&](int b, int64_t r, int64_t r_next) {
+    // Wait here, on every path, for all of buffer b: otherwise the compiler, which places its
+    // waits per path, waits again further down, behind the request for the next row, and the
+    // memory counter being in order that wait would also cover the request.
+    asm volatile("" ::"v"(st.rstd[b]));
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch) {
+      asm volatile("" ::"v"(st.dy[b][ch][0]), "v"(st.dy[b][ch][1]), "v"(st.cw[b][ch][0]),
+                   "v"(st.cw[b][ch][1]), "v"(st.cw[b][ch][2]), "v"(st.cw[b][ch][3]),
+                   "v"(st.cw[b][ch][4]), "v"(st.cs[b][ch]));
+    }
+    if (r_next < p.rows) request(b ^ 1, r_next);
+    float m = 0.0f;
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch) {
+      if (st.live[ch]) {
+        const v4u wv[2] = {wl[(2 * ch) * kTeamThreads + t], wl[(2 * ch + 1) * kTeamThreads + t]};
+#pragma unroll
+        for (int i = 0; i < kValsPerLane; ++i) {
+          float dyf, wf, xh;
+          decode(b, ch, i, wv, dyf, wf, xh);
+          m = __builtin_fmaf(dyf * wf, xh, m);
+        }
+      }
+    }
+    m = wave_sum(m);
+    if ((t & 63) == 0) red[t >> 6] = m;
+    __syncthreads();
+    m = (red[0] + red[1]) + (red[2] + red[3]);
+    m = __fdiv_rn(m, (float)p.cols);
+    const float rstd = st.rstd[b];
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch) {
+      if (st.live[ch]) {
+        const v4u wv[2] = {wl[(2 * ch) * kTeamThreads + t], wl[(2 * ch + 1) * kTeamThreads + t]};
+        float dx[kValsPerLane];
+#pragma unroll
+        for (int i = 0; i < kValsPerLane; ++i) {
+          float dyf, wf, xh;
+          decode(b, ch, i, wv, dyf, wf, xh);
+          dx[i] = rstd * (dyf * wf - xh * m);
+          st.dwacc[ch][i] = __builtin_fmaf(dyf, xh, st.dwacc[ch][i]);
+        }
+        v4u lo, hi;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          lo[i] = pack_bf16x2(dx[2 * i], dx[2 * i + 1]);
+          hi[i] = pack_bf16x2(dx[8 + 2 * i], dx[8 + 2 * i + 1]);
+        }
+        v4u* o = reinterpret_cast<v4u*>(p.dx + r * p.ldo + st.c0[ch]);
+        o[0] = lo;
+        o[1] = hi;
+      }
+    }
+    __syncthreads();
+  };
+  // The workgroup's rows part, part + n_parts, ... alternate between the teams; team 0 has the
+  // first and therefore at least as many as team 1, which starts one step later.  Both teams
+  // pass the same number of barriers: 2 n0 + 1, n0 = team 0's rows.
+  const int64_t stride = 2 * (int64_t)p.n_parts, first_row = part + (int64_t)kTeam * p.n_parts;
+  const int64_t n0 = part < p.rows ? (p.rows - 1 - part) / stride + 1 : 0;
+  const int64_t mine = first_row < p.rows ? (p.rows - 1 - first_row) / stride + 1 : 0;
+  if (n0 == 0) return;
+  if (mine > 0) request(0, first_row);
+  if (kTeam == 1) __syncthreads();
+  int64_t r = first_row;
+  for (int64_t k = 0; k + 1 < mine; k += 2, r += 2 * stride) {
+    row(0, r, r + stride);
+    row(1, r + stride, r + 2 * stride);
+  }
+  if (mine & 1) row(0, r, p.rows);
+  for (int64_t left = 2 * n0 + 1 - kTeam - 2 * mine; left > 0; --left) __syncthreads();
+}
+
+template <int kCh>
+__global__ __launch_bounds__(2 * kTeamThreads, 2) void rmsnorm_backward_pair_kernel(RmsParams p) {
+  __shared__ float red[2][kTeamThreads / 64];
+  // the gain as loaded (bf16 pairs, 32 bytes per thread and chunk) while the rows are processed,
+  // then team 1's column sums
+  __shared__ __align__(16) float shared[kCh * kValsPerLane * kTeamThreads];
+  v4u* wl = reinterpret_cast<v4u*>(shared);
+  float (*dwx)[kTeamThreads] = reinterpret_cast<float (*)[kTeamThreads]>(shared);
+  const int part = blockIdx.x;
+  const int team = (int)(threadIdx.x / kTeamThreads);      // the same for a whole wavefront
+  const int t = (int)(threadIdx.x % kTeamThreads);
+  const int s = t % kLanesPerGroup;
+  PairState<kCh> st;
+#pragma unroll
+  for (int ch = 0; ch < kCh; ++ch) {
+    const int j = ch * kTeamGroups + t / kLanesPerGroup;
+    const int c = j * kCtxGroup + s * kValsPerLane;
+    st.live[ch] = j < p.ng && c < p.cols;
+    st.grp[ch] = st.live[ch] ? j : 0;     // a dead lane reads the row's first values and drops them
+    st.c0[ch] = st.live[ch] ? c : 0;
+    if (team == 0) {
+      const v4u* v = reinterpret_cast<const v4u*>(p.w + st.c0[ch]);
+      wl[(2 * ch) * kTeamThreads + t] = v[0];
+      wl[(2 * ch + 1) * kTeamThreads + t] = v[1];
+    }
+#pragma unroll
+    for (int i = 0; i < kValsPerLane; ++i) st.dwacc[ch][i] = 0.0f;
+  }
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch) {
+      st.dy[b][ch][0] = st.dy[b][ch][1] = v4u{0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int i = 0; i < 5; ++i) st.cw[b][ch][i] = 0u;
+      st.cs[b][ch] = 0.0f;
+    }
+    st.rstd[b] = 0.0f;
+  }
+  __syncthreads();
+  if (team == 0) pair_team_rows<kCh, 0>(p, st, red[0], wl, part, t, s);
+  else pair_team_rows<kCh, 1>(p, st, red[1], wl, part, t, s);
+  if (team == 1) {
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch)
+#pragma unroll
+      for (int i = 0; i < kValsPerLane; ++i) dwx[ch * kValsPerLane + i][t] = st.dwacc[ch][i];
+  }
+  __syncthreads();
+  if (team == 0) {
+#pragma unroll
+    for (int ch = 0; ch < kCh; ++ch) {
+      if (!st.live[ch]) continue;
+      float* dst = p.dw_parts + (int64_t)part * p.cols + st.c0[ch];
+#pragma unroll
+      for (int i = 0; i < kValsPerLane; ++i) dst[i] = st.dwacc[ch][i] + dwx[ch * kValsPerLane + i][t];
+    }
+  }
+}
+
 // dw[c] = sum of the partial sums, in a fixed order: thread (slice k of 16, column c) adds the
 // parts k, k + 16, k + 32, ... into eight interleaved running sums (eight loads in flight), folds
 // them pairwise, and the sixteen slice sums of a column are folded pairwise in slice order.
@@ -571,9 +776,15 @@ hipError_t launch_rmsnorm(const RmsParams& p, bool backward, hipStream_t st) {
   if (p.rows > 0 && bwd_chunks <= kBwdMaxChunks) {
     const dim3 grid((unsigned)p.n_parts), block(kBwdThreads);
     const bool vec = p.vec_ok && p.vec_w && p.cols % kValsPerLane == 0;
-    if (bwd_chunks == 1) {
-      if (vec) hipLaunchKernelGGL((rmsnorm_backward_row_kernel<1, true>), grid, block, 0, st, p);
-      else hipLaunchKernelGGL((rmsnorm_backward_row_kernel<1, false>), grid, block, 0, st, p);
+    const dim3 pair(2 * kTeamThreads);
+    if (vec && p.ng <= kTeamGroups) {
+      hipLaunchKernelGGL((rmsnorm_backward_pair_kernel<1>), grid, pair, 0, st, p);
+    } else if (vec && p.ng <= 2 * kTeamGroups) {
+      hipLaunchKernelGGL((rmsnorm_backward_pair_kernel<2>), grid, pair, 0, st, p);
+    } else if (vec && p.ng <= kTeamMaxChunks * kTeamGroups) {
+      hipLaunchKernelGGL((rmsnorm_backward_pair_kernel<3>), grid, pair, 0, st, p);
+    } else if (bwd_chunks == 1) {
+      hipLaunchKernelGGL((rmsnorm_backward_row_kernel<1, false>), grid, block, 0, st, p);
     } else {
       if (vec) hipLaunchKernelGGL((rmsnorm_backward_row_kernel<2, true>), grid, block, 0, st, p);
       else hipLaunchKernelGGL((rmsnorm_backward_row_kernel<2, false>), grid, block, 0, st, p);

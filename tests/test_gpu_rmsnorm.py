@@ -54,7 +54,11 @@ def _case(rows, cols, seed):
 
 
 @pytest.mark.parametrize("shape,parts", [((64, 512), 16), ((33, 300), 7), ((1, 1), 1), ((5, 4097), 3),
-                                          ((300, 136), 256), ((9, 11008), 4), ((2, 16384), 5), ((3, 20000), 2)])
+                                          ((300, 136), 256), ((9, 11008), 4), ((2, 16384), 5), ((3, 20000), 2),
+                                          # 16-byte rows whose last group is ragged; one, two and three
+                                          # 4096-column chunks; fewer rows than parts
+                                          ((37, 4112), 5), ((21, 11024), 4), ((12, 12288), 3), ((3, 2048), 8),
+                                          ((70, 8192), 8), ((1, 4096), 1)])
 def test_rmsnorm_forward_backward(shape, parts):
     rows, cols = shape
     bx, bw, bdy = _case(rows, cols, seed=rows + cols)
