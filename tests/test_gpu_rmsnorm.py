@@ -131,3 +131,33 @@ def test_rmsnorm_strides_determinism_and_errors():
                                  C.c_void_p(dw.data_ptr()), C.c_void_p(parts.data_ptr()), 2, st) == fq.FQ_OK
     torch.cuda.synchronize()
     assert torch.all(dw == 0).item()
+
+
+@pytest.mark.parametrize("cols,ld,off", [(4112, 4224, 0), (4112, 4224, 8), (4112, 4224, 3), (8192, 8196, 0)])
+def test_rmsnorm_backward_pitched(cols, ld, off):
+    """dy and dx as column windows of wider matrices: 16-byte pitch and offset (the two-team
+    kernel), a pitch or offset that is not (the general kernel); both against the contiguous call."""
+    rows = 45
+    bx, bw, bdy = _case(rows, cols, seed=cols + off)
+    wd = gu.to_device_bf16(bw.reshape(1, -1)).reshape(-1)
+    y, rstd, ctx = fq.fq_rmsnorm_forward(gu.to_device_bf16(bx), wd, 1e-5)
+    dy = gu.to_device_bf16(bdy)
+    gu.announce(f"rmsnorm backward pitched cols={cols} ld={ld} off={off}")
+    ref_dx, ref_dw = fq.fq_rmsnorm_backward(dy, ctx, rstd, wd, n_parts=6)
+    wide = torch.zeros((rows, ld), dtype=torch.bfloat16, device="cuda")
+    wide[:, off:off + cols] = dy
+    out = torch.full((rows, ld), 7.0, dtype=torch.bfloat16, device="cuda")
+    dw = torch.empty((cols,), dtype=torch.float32, device="cuda")
+    fq.fq_rmsnorm_backward_static(wide[:, off:off + cols], ctx, rstd, wd, out[:, off:off + cols], dw, n_parts=6)
+    torch.cuda.synchronize()
+    got = out[:, off:off + cols]
+    assert (out[:, :off] == 7.0).all().item() and (out[:, off + cols:] == 7.0).all().item()
+    if off % 8 == 0 and ld % 8 == 0:
+        assert torch.equal(got, ref_dx)          # the same kernel: the same bits
+    else:
+        # the general kernel sums a row's mean in another order: a last-place difference in the
+        # mean moves few dx values by one bf16 step
+        differ = (got != ref_dx)
+        assert differ.float().mean().item() < 0.01
+        assert ((got.float() - ref_dx.float()).abs() <= 2.0 ** -7 * ref_dx.float().abs() + 1e-30).all().item()
+    assert torch.allclose(dw, ref_dw, rtol=1e-5, atol=1e-6)
