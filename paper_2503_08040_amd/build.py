@@ -46,6 +46,8 @@ ABLATIONS = {
     "extra_salu_40": ["-DFQ_ABLATE_EXTRA_SALU=40"],
     "extra_salu_120": ["-DFQ_ABLATE_EXTRA_SALU=120"],
     "one_stager": ["-DFQ_ABLATE_ONE_STAGER"],
+    "team_skew": ["-DFQ_ABLATE_TEAM_SKEW"],
+    "team_skew_no_dma": ["-DFQ_ABLATE_TEAM_SKEW", "-DFQ_ABLATE_NO_DMA"],
 }
 
 

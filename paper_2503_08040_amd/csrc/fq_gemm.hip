@@ -50,6 +50,13 @@
 //   FQ_ABLATE_NO_DEQUANT    the MFMAs and their LDS reads, without the converts and FMAs
 //   FQ_ABLATE_EXTRA_SALU=n  n dependent scalar additions behind every barrier of the k-loop
 //   FQ_ABLATE_ONE_STAGER    wavefronts 0-3 (one per SIMD) issue all loads, 16 each, 4-7 none
+//   FQ_ABLATE_TEAM_SKEW     (computes the right products) the two wavefronts of a SIMD half an item
+//                           apart in the 2 x 2 geometry: the wavefronts of i-block 0 and of i-block
+//                           1 form two teams with two barriers per item, each the item boundary of
+//                           one team and the middle of the item of the other; a team loads its own
+//                           A block, team 0 the B blocks as well.  The B operands of an item sit in
+//                           registers after its first two units, which is why two ring slots still
+//                           suffice.
 namespace fq {
 
 namespace {
@@ -88,6 +95,24 @@ __device__ inline void stage_half_block(const int8_t* src, int8_t* lds_dst, int 
     __builtin_amdgcn_global_load_lds(g, l, 16, 2 * kFragBytes, 0);
     __builtin_amdgcn_global_load_lds(g, l, 16, 3 * kFragBytes, 0);
   }
+}
+
+// One wavefront copies 4 KiB (4 fragments) global -> LDS: one group of stage_half_block.
+__device__ inline void stage_quarter_block(const int8_t* src, int8_t* lds_dst, int lane) {
+  const unsigned voff = (unsigned)lane * 16u;
+  const uint64_t a = reinterpret_cast<uint64_t>(src);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+  src = reinterpret_cast<const int8_t*>(((uint64_t)hi << 32) | lo);
+#ifdef FQ_ABLATE_NO_DMA
+  if (voff != 0xFFFFFFFFu) return;
+#endif
+  gbl_void* g = (gbl_void*)(src + voff);
+  lds_void* l = (lds_void*)lds_dst;
+  __builtin_amdgcn_global_load_lds(g, l, 16, 0 * kFragBytes, 0);
+  __builtin_amdgcn_global_load_lds(g, l, 16, 1 * kFragBytes, 0);
+  __builtin_amdgcn_global_load_lds(g, l, 16, 2 * kFragBytes, 0);
+  __builtin_amdgcn_global_load_lds(g, l, 16, 3 * kFragBytes, 0);
 }
 
 // two floats -> two bf16 (round-to-nearest-even) in one dword, low half first
@@ -335,6 +360,11 @@ template <class G, bool kBiased>
 __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int jb_first,
                                           int8_t* lds) {
   constexpr int kBI = G::kBI, kBJ = G::kBJ, kSI = G::kSI, kSJ = G::kSJ, kUnits = G::kUnits;
+#ifdef FQ_ABLATE_TEAM_SKEW
+  constexpr bool kSkew = kBI == 2 && kBJ == 2;
+#else
+  constexpr bool kSkew = false;
+#endif
   int8_t* const a_ring = lds;                    // [2][kBI blocks]
   int8_t* const b_ring = lds + 2 * G::kASet;     // [2][kBJ blocks]
 
@@ -448,6 +478,26 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
 #endif
     }
   };
+  // kSkew: this wavefront's share of item (k, res) when the two teams (h = 0, 1: the wavefronts
+  // of i-block h, one per SIMD each) run half an item apart: a quarter of its own team's A block,
+  // and for team 0 half a B block as well.
+  auto stage_team = [&](int k, int res, const KRec<G>& r, int asel, bool new_b) {
+    int blk = ib[0], s = r.slot[0];
+#pragma unroll
+    for (int i = 1; i < kBI; ++i) if (h == i) { blk = ib[i]; s = r.slot[i]; }
+    const int quarter = c * (kBlockBytes / 4);
+    int8_t* const dst = a_ring + asel * G::kASet + h * kBlockBytes + quarter;
+    if (!res) stage_quarter_block(p.a_codes + ((int64_t)blk * p.nkb + k) * kBlockBytes + quarter, dst, lane);
+    else if (s >= 0) stage_quarter_block(p.a_res + (int64_t)s * kBlockBytes + quarter, dst, lane);
+    if (h == 0 && new_b) {
+      int jb = jbt[0];
+#pragma unroll
+      for (int j = 1; j < kBJ; ++j) if ((c >> 1) == j) jb = jbt[j];
+      const int part = (c >> 1) * kBlockBytes + (c & 1) * (kBlockBytes / 2);
+      stage_half_block(p.b_codes + ((int64_t)jb * p.nkb + k) * kBlockBytes + (c & 1) * (kBlockBytes / 2),
+                       b_ring + (k & 1) * G::kBSet + part, lane);
+    }
+  };
   // scale column sc belongs to the wave's second j-block?
   auto sc_is_hi = [&](int scol) { return ((kSJ * c + scol) >> 2) != jlo; };
 
@@ -484,8 +534,12 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
     // records are fetched two k-blocks ahead so that no scalar load is waited for in the loop
     KRec<G> r0 = load_rec(0), r1 = load_rec(1), r2 = load_rec(2);
     int k = 0, res = 0, t = 0;
-    stage_item(0, 0, r0, 0, true);
-    {
+    if constexpr (kSkew) {
+      stage_team(0, 0, r0, 0, true);
+      if (any_flagged(r0)) stage_team(0, 1, r0, 1, false);
+      else if (1 < nkb) stage_team(1, 0, r1, 1, true);
+    } else {
+      stage_item(0, 0, r0, 0, true);
       if (any_flagged(r0)) stage_item(0, 1, r0, 1, false);
       else if (1 < nkb) stage_item(1, 0, r1, 1, true);
     }
@@ -512,6 +566,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
     for (int i = 0; i < G::kSP; ++i) sp[i] = 0.0f;
 
     int late_b_k = -1;     // B stagers: k-block whose B set is still to be requested (-1: none)
+    if (kSkew && h == 1) asm volatile("s_barrier" ::: "memory");   // team 1 starts one barrier later
     for (;;) {
       // The B stagers request their blocks here, two units after the barrier that freed the
       // ring slot, not right behind it: right after the barrier the four A stagers (one per
@@ -555,7 +610,18 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
       const int8_t* const a_nxt = a_ring + ((t + 1) & 1) * G::kASet;
       const int8_t* const b_nxt = b_ring + (n1k & 1) * G::kBSet;
 
-      if (active) run_units_range<G, 0, kUnits - 2, kBiased>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp, magic);
+      if constexpr (kSkew) {
+        // two barriers per item: this one is the other team's item boundary, in the middle of ours
+        if (active) run_units_range<G, 0, 2, kBiased>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp, magic);
+        // Behind this barrier team 0 may overwrite the B set this wavefront took its operands
+        // from.  An active wavefront has multiplied with all of them by now; one that skips the
+        // item has not used them yet and waits for the reads here.
+        else __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0)
+        asm volatile("s_barrier" ::: "memory");
+        if (active) run_units_range<G, 2, kUnits - 2, kBiased>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp, magic);
+      } else {
+        if (active) run_units_range<G, 0, kUnits - 2, kBiased>(st, a_cur, a_nxt, b_nxt, h, c, lane, sc, sp, magic);
+      }
 
       // All LDS reads of this item are issued (the last two units run from registers).  Wait
       // for them and for the next item's direct-to-LDS loads, then the barrier publishes the
@@ -577,7 +643,10 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
       }
 #else
       if (has2) {
-        if (stage_a) {
+        if constexpr (kSkew) {
+          if (n2res) stage_team(k + 1, 1, r1, t & 1, false);
+          else stage_team(n2k, 0, r1, t & 1, n2k != n1k);
+        } else if (stage_a) {
           if (n2res) stage_item(k + 1, 1, r1, t & 1, false);
           else stage_item(n2k, 0, r1, t & 1, false);
         } else if (!n2res && n2k != n1k) {
@@ -632,6 +701,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
         r2 = load_rec(k + 2);
       }
     }
+    if (kSkew && h == 0) asm volatile("s_barrier" ::: "memory");   // team 1's last item boundary
     drain<G, kBiased>(st, sp);
     if constexpr (kBiased) remove_bias();
   }

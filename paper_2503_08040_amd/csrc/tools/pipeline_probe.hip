@@ -40,7 +40,12 @@ constexpr size_t kFarBytes = 128u << 20;  // second source behind the window: to
 // 8 units (right behind the barrier when BAR is set), 3 = the eight over the first six of every 8
 // units, so that the last has two units to land before the wait that precedes the barrier, 4 = half
 // the wavefronts (one per SIMD) one per unit and the other half two per unit in the first 4 of 8.  BAR: 1 = s_barrier every 8 units.
-template <int AB, int NF, int NC, int R, int SS, int CV, int kThreads, int D = 0, int BAR = 0>
+// D = 6: the two wavefronts of a SIMD half an item apart (wavefronts 0-3 and 4-7 as two teams): a
+// barrier every 4 units, which is the item boundary (wait for the loads, burst of 8 loads) of one
+// team and the middle of the item of the other, alternately.
+// SW: 1 = at its item boundary a wavefront reads its first operands again behind the barrier and waits
+// for them, as a k-loop must whose next ring slot only becomes valid at the barrier.
+template <int AB, int NF, int NC, int R, int SS, int CV, int kThreads, int D = 0, int BAR = 0, int SW = 0>
 __global__ __launch_bounds__(kThreads, 1) void probe(const v4i* in, float* out, uint64_t* stamps, float s, int trips,
                                                      const int8_t* window, int far_every) {
   extern __shared__ __attribute__((aligned(1024))) int8_t lds[];
@@ -105,11 +110,30 @@ __global__ __launch_bounds__(kThreads, 1) void probe(const v4i* in, float* out, 
     for (int u = 0; u < kUnits; ++u) {
       const int cur = u & 1, nxt = cur ^ 1;
       if (R > 0) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      if (u == 0 && (it & 1) == 0) {
+      auto switch_slot = [&]() {
+        if (SW && !AB) {
+#pragma unroll
+          for (int n = 0; n < R; ++n)
+            asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(fr[0][n]) : "v"(lds_addr), "n"(n * 1024));
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+      };
+      if (D == 6) {
+        if (u == 0) {
+          const bool boundary = ((it + (w >> 2)) & 1) == 0;      // of this wavefront's team
+          if (boundary) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          asm volatile("s_barrier" ::: "memory");
+          if (boundary) {
+            for (int i = 0; i < 8; ++i) dma(it * 4 + i);
+            switch_slot();
+          }
+        }
+      } else if (u == 0 && (it & 1) == 0) {
         // every 8 units: what the k-loop of the GEMM does once per item
         if (D) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         if (BAR) asm volatile("s_barrier" ::: "memory");
         if (D == 2) for (int i = 0; i < 8; ++i) dma(it * 4 + i);
+        switch_slot();
       }
       if (D == 1) dma(it * kUnits + u);
       if (D == 3) {   // the 8 loads over the first 6 of the 8 units: 2 2 1 1 1 1 0 0
@@ -411,6 +435,11 @@ int main() {
   time_kernel(probe<0, 2, 2, 3, 0, 0, 512, 4, 1>, 512, kUnits, "mfma16_2fma_2cvt_3reads_dma_mixed_barrier", "barrier every 8 units + per SIMD one wavefront 1 load per unit, the other 2 per unit in the first 4 units");
   time_kernel(probe<0, 2, 2, 3, 0, 0, 512, 5, 0>, 512, kUnits, "mfma16_2fma_2cvt_3reads_partner_requests", "one wavefront per SIMD computes (cycles are its own, 1 wavefront), its partner only issues direct-to-LDS loads back to back");
   time_kernel(probe<0, 0, 0, 3, 0, 0, 512, 2, 1>, 512, kUnits, "mfma16_3reads_dma_burst_barrier", "MFMA + reads + barrier + burst loads, no dequantization");
+  time_kernel(probe<0, 2, 2, 3, 0, 0, 512, 2, 1, 1>, 512, kUnits, "mfma16_2fma_2cvt_3reads_dma_burst_barrier_switch", "the GEMM's k-loop + the first operand reads of an item behind its barrier");
+  time_kernel(probe<0, 2, 2, 3, 0, 0, 512, 6, 1, 0>, 512, kUnits, "mfma16_2fma_2cvt_3reads_teams_half_item_apart", "the two wavefronts of a SIMD half an item apart: barrier every 4 units, burst of 8 loads at a wavefront's own item boundary");
+  time_kernel(probe<0, 2, 2, 3, 0, 0, 512, 6, 1, 1>, 512, kUnits, "mfma16_2fma_2cvt_3reads_teams_half_item_apart_switch", "the same + the first operand reads of an item behind its barrier");
+  time_kernel(probe<0, 2, 2, 3, 0, 0, 512, 2, 1, 1>, 512, kUnits, "mfma16_2fma_2cvt_3reads_dma_burst_barrier_switch_far8", "the GEMM's k-loop + first reads behind the barrier, every 8th load misses the L2", 8);
+  time_kernel(probe<0, 2, 2, 3, 0, 0, 512, 6, 1, 1>, 512, kUnits, "mfma16_2fma_2cvt_3reads_teams_half_item_apart_switch_far8", "teams half an item apart + first reads behind the barrier, every 8th load misses the L2", 8);
   time_kernel(probe<0, 2, 2, 0, 0, 0, 256>, 256, kUnits, "mfma16_2fma_2cvt_1wave", "exact dequantization, one wavefront per SIMD");
   time_kernel(probe32<0, 1, 512>, 512, 4, "mfma32_only", "4 MFMA 32x32x32 per unit, nothing else");
   time_kernel(probe32<6, 1, 512>, 512, 4, "mfma32_6valu", "per MFMA 32x32x32: 3 FMA + 3 converts");
