@@ -45,6 +45,7 @@ ABLATIONS = {
     "no_dequant": ["-DFQ_ABLATE_NO_DEQUANT"],
     "extra_salu_40": ["-DFQ_ABLATE_EXTRA_SALU=40"],
     "extra_salu_120": ["-DFQ_ABLATE_EXTRA_SALU=120"],
+    "dma_hot": ["-DFQ_ABLATE_DMA_HOT"],
     "one_stager": ["-DFQ_ABLATE_ONE_STAGER"],
     "team_skew": ["-DFQ_ABLATE_TEAM_SKEW"],
     "team_skew_no_dma": ["-DFQ_ABLATE_TEAM_SKEW", "-DFQ_ABLATE_NO_DMA"],

@@ -49,6 +49,8 @@
 //   FQ_ABLATE_NO_MULTIPLY   no wavefront multiplies: loads, waits, barriers and epilogue only
 //   FQ_ABLATE_NO_DEQUANT    the MFMAs and their LDS reads, without the converts and FMAs
 //   FQ_ABLATE_EXTRA_SALU=n  n dependent scalar additions behind every barrier of the k-loop
+//   FQ_ABLATE_DMA_HOT       every global -> LDS load reads from the first MiB of the A codes (which
+//                           must be that large), so that all of them hit the L2
 //   FQ_ABLATE_ONE_STAGER    wavefronts 0-3 (one per SIMD) issue all loads, 16 each, 4-7 none
 //   FQ_ABLATE_TEAM_SKEW     (computes the right products) the two wavefronts of a SIMD half an item
 //                           apart in the 2 x 2 geometry: the wavefronts of i-block 0 and of i-block
@@ -466,12 +468,20 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
       } else {
         src = smain + (int64_t)k * kBlockBytes;
       }
+#ifdef FQ_ABLATE_DMA_HOT
+      src = p.a_codes + (reinterpret_cast<uintptr_t>(src) & 0xFE000u);
+#endif
       stage_half_block(src, a_ring + asel * G::kASet + soff, lane);
 #ifdef FQ_ABLATE_ONE_STAGER
       stage_half_block(src + kBlockBytes / 2, a_ring + asel * G::kASet + soff + kBlockBytes / 2, lane);
 #endif
     } else if (new_b) {
+#ifdef FQ_ABLATE_DMA_HOT
+      stage_half_block(p.a_codes + (reinterpret_cast<uintptr_t>(smain + (int64_t)k * kBlockBytes) & 0xFE000u),
+                       b_ring + (k & 1) * G::kBSet + soff, lane);
+#else
       stage_half_block(smain + (int64_t)k * kBlockBytes, b_ring + (k & 1) * G::kBSet + soff, lane);
+#endif
 #ifdef FQ_ABLATE_ONE_STAGER
       stage_half_block(smain + (int64_t)k * kBlockBytes + kBlockBytes / 2,
                        b_ring + (k & 1) * G::kBSet + soff + kBlockBytes / 2, lane);
@@ -574,8 +584,14 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, int ib_first, int
       // address unit to take them, the B stagers, which share their SIMDs, run the last two
       // units of the item.  With all 64 loads issued at once, both wavefronts of every SIMD sat
       // blocked and the matrix cores idled for about a fifth of every item.
-      if (late_b_k >= 0)
+      if (late_b_k >= 0) {
+#ifdef FQ_ABLATE_DMA_HOT
+        stage_half_block(p.a_codes + (reinterpret_cast<uintptr_t>(smain + (int64_t)late_b_k * kBlockBytes) & 0xFE000u),
+                         b_ring + (late_b_k & 1) * G::kBSet + soff, lane);
+#else
         stage_half_block(smain + (int64_t)late_b_k * kBlockBytes, b_ring + (late_b_k & 1) * G::kBSet + soff, lane);
+#endif
+      }
       late_b_k = -1;
       // ---- the items after this one (all wave-uniform scalar logic)
       const bool n1res = !res && any_flagged(r0);
