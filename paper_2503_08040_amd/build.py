@@ -10,8 +10,13 @@ HEADERS = ["fq_device.h", "fq_kernels.h", os.path.join("..", "..", "include", "f
 
 # Packed FP32 VALU instructions are switched off for the device pass (the host
 # pass prints a harmless "not a recognized feature" note).
+# -amdgpu-atomic-optimizer-strategy=None: the compiler otherwise turns an atomic issued by one
+# thread into its wavefront-aggregated form, whose result is broadcast (and therefore waited for)
+# right behind the instruction; the quantizer issues its atomics early precisely so that their
+# round trip passes behind the arithmetic that follows.
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
                "-Wall", "-Wno-unused-command-line-argument"]
 
 

@@ -351,6 +351,9 @@ void quantize_kernel(QuantParams p) {
     if (t == 0) {
       const int nb = (int)gridDim.x, g = blk >> 5;
       const uint32_t full = (nb - 32 * g >= 32) ? 0xFFFFFFFFu : ((1u << (nb - 32 * g)) - 1u);
+      // (both halves of the returned word are named here: a half that nothing reads gives its
+      // register away at once, and the write to that register would wait for the atomic)
+      asm volatile("" ::"v"(group_before));
       const uint32_t decided = (uint32_t)group_before | (1u << (blk & 31));
       bool last = false;
       if (decided == full) last = atomicAdd(p.fb_groups_done, 1) == ((nb + 31) >> 5) - 1;
