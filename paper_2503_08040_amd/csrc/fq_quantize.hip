@@ -326,22 +326,33 @@ void quantize_kernel(QuantParams p) {
     }
   }
 
-  // ---- per-block outputs.  Runs before the block's codes are stored (the atomics issued
-  // after the decision have had the whole quantization to come back, and no store is pending
-  // that the wait for them would have to sit out); with an error-based criterion the decision
-  // is only known after the codes, so it runs there.
+  // ---- the block's residual slot, known to the whole workgroup before the codes are stored (the
+  // atomic issued after the decision has had the whole quantization to come back; an unflagged
+  // block does not look at it at all); with an error-based criterion the decision is only known
+  // after the codes, so this runs there.
   int slot = -1;
   auto record_block = [&]() {
     if (t == 0) {
-      const int slot0 = u ? ((slot_early < p.capacity) ? slot_early : -2) : -1;
-      p.scales[blk] = a;
-      p.mask[blk] = u ? 1 : 0;
-      p.fb_slot[blk] = slot0;
-      if (blk == 0) *p.fb_count_next = 0;   // ready for the next call into this tensor
+      int slot0 = -1;
+      if (u) {
+        asm volatile("" : "+v"(slot_early));     // keeps the wait for the atomic inside this branch
+        slot0 = (slot_early < p.capacity) ? slot_early : -2;
+      }
       slot_sh = slot0;
     }
     __syncthreads();
     slot = slot_sh;
+  };
+  // ---- per-block outputs: scale, mask, slot.  Stored last, when the wavefront has nothing left
+  // to compute: a register that held store data is not reused before the store has completed,
+  // and behind these small stores that wait sat in the middle of the quantization.
+  auto store_block_record = [&]() {
+    if (t == 0) {
+      p.scales[blk] = a;
+      p.mask[blk] = u ? 1 : 0;
+      p.fb_slot[blk] = slot;
+      if (blk == 0) *p.fb_count_next = 0;   // ready for the next call into this tensor
+    }
   };
   // ---- the list of flagged blocks: the workgroup whose decision completed a group of 32 counts
   // the group, the one that counts the last group writes the list.  Runs when the workgroup has
@@ -403,6 +414,7 @@ void quantize_kernel(QuantParams p) {
 
   if (kErr) record_block();
   if (slot < 0) {        // uniform over the workgroup
+    store_block_record();
     finish_list();
     return;
   }
@@ -435,6 +447,7 @@ void quantize_kernel(QuantParams p) {
     *reinterpret_cast<v4i*>(rdst + tile_offset(pz * 32 + rp, cc * 16)) = rq[pz];
   if (kWantT) store_transposed(rq, rp, cc, img, p.res_codes_t + (int64_t)slot * kBlockBytes);
   if (t == 0) p.res_scales[slot] = ra;
+  store_block_record();
   finish_list();
 }
 
