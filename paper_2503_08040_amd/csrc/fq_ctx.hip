@@ -244,6 +244,76 @@ __global__ __launch_bounds__(kCtxThreads) void glu_backward_kernel(GluParams p) 
   store16(p.dx2 + q.r * p.ldo + q.c0, p.vec_ok, q.c0, p.cols, d2);
 }
 
+// The two kernels above for matrices that allow 16-byte accesses with cols a multiple of 16 (a
+// live lane then owns 16 whole values).  Every load of a thread is issued before the first value
+// is used: in the general form each operand's loads sit in a branch of their own together with
+// their unpacking, so one operand had arrived before the next was requested.  A lane without
+// values reads the first values of its row and drops them.
+__global__ __launch_bounds__(kCtxThreads) void glu_forward_vec_kernel(GluParams p) {
+  const LanePos q = lane_pos(p.n_groups, p.ng);
+  const bool on = q.live && q.c0 < p.cols;
+  const int c = on ? q.c0 : 0;
+  const v4u* a1 = reinterpret_cast<const v4u*>(p.x1 + q.r * p.ld + c);
+  const v4u* a2 = reinterpret_cast<const v4u*>(p.x2 + q.r * p.ld + c);
+  v4u r1[2], r2[2];
+  r1[0] = __builtin_nontemporal_load(a1);
+  r1[1] = __builtin_nontemporal_load(a1 + 1);
+  r2[0] = __builtin_nontemporal_load(a2);
+  r2[1] = __builtin_nontemporal_load(a2 + 1);
+  const v4u zero4 = {0u, 0u, 0u, 0u};
+  if (!on) r1[0] = r1[1] = r2[0] = r2[1] = zero4;
+  float x1[kValsPerLane], x2[kValsPerLane], y[kValsPerLane];
+  unpack16(r1, x1);
+  unpack16(r2, x2);
+#pragma unroll
+  for (int i = 0; i < kValsPerLane; ++i) y[i] = x1[i] * logistic(x1[i]) * x2[i];
+  if (on) store16(p.y + q.r * p.ldy + q.c0, true, q.c0, p.cols, y);
+  quantize_store(x1, q, p.packed1, p.scales1);
+  quantize_store(x2, q, p.packed2, p.scales2);
+}
+
+// the 5 dwords of this lane's 16 ten-bit fields -> scale * code
+__device__ inline void dequantize16(const uint32_t (&w)[5], float a, float (&v)[kValsPerLane]) {
+#pragma unroll
+  for (int i = 0; i < kValsPerLane; ++i) {
+    const int pos = 10 * i, word = pos >> 5, sh = pos & 31;
+    uint32_t bits = w[word] >> sh;
+    if (sh > 22) bits |= w[word + 1] << (32 - sh);
+    const int code = (int)(bits << 22) >> 22;   // sign-extend the 10-bit field
+    v[i] = a * (float)code;
+  }
+}
+
+__global__ __launch_bounds__(kCtxThreads) void glu_backward_vec_kernel(GluParams p) {
+  const LanePos q = lane_pos(p.n_groups, p.ng);
+  if (!q.live || q.c0 >= p.cols) return;
+  const v4u* ad = reinterpret_cast<const v4u*>(p.dy + q.r * p.ld_dy + q.c0);
+  const uint32_t* s1 = reinterpret_cast<const uint32_t*>(p.packed1 + q.g * kCtxGroupBytes) + q.s * 5;
+  const uint32_t* s2 = reinterpret_cast<const uint32_t*>(p.packed2 + q.g * kCtxGroupBytes) + q.s * 5;
+  v4u rd[2];
+  uint32_t w1[5], w2[5];
+  rd[0] = ad[0];
+  rd[1] = ad[1];
+#pragma unroll
+  for (int i = 0; i < 5; ++i) w1[i] = __builtin_nontemporal_load(s1 + i);
+#pragma unroll
+  for (int i = 0; i < 5; ++i) w2[i] = __builtin_nontemporal_load(s2 + i);
+  const float sa1 = p.scales1[q.g], sa2 = p.scales2[q.g];
+  float dy[kValsPerLane], x1[kValsPerLane], x2[kValsPerLane];
+  unpack16(rd, dy);
+  dequantize16(w1, sa1, x1);
+  dequantize16(w2, sa2, x2);
+  float d1[kValsPerLane], d2[kValsPerLane];
+#pragma unroll
+  for (int i = 0; i < kValsPerLane; ++i) {
+    const float s = logistic(x1[i]);
+    d2[i] = dy[i] * (x1[i] * s);
+    d1[i] = dy[i] * x2[i] * (s * (1.0f + x1[i] * (1.0f - s)));
+  }
+  store16(p.dx1 + q.r * p.ldo + q.c0, true, q.c0, p.cols, d1);
+  store16(p.dx2 + q.r * p.ldo + q.c0, true, q.c0, p.cols, d2);
+}
+
 // ---- RMS normalization with a fused INT10 context --------------------------------------------
 // One 256-thread workgroup walks a row in chunks of 32 groups (4096 columns): thread t is lane
 // t % 8 of group t / 8 of the chunk, the same team layout as above.
@@ -334,6 +404,59 @@ __global__ __launch_bounds__(kCtxThreads) void rmsnorm_forward_kernel(RmsParams 
       load16(p.x + r * p.ld + q.c0, q.live, p.vec_ok, q.c0, p.cols, xc);
       finish(ch, xc);
     }
+  }
+}
+
+// The forward kernel for rows of kCh chunks whose matrices and gain allow 16-byte accesses, cols a
+// multiple of 16: the loads of the whole row are issued before the first value is used (in the
+// general form every chunk's loads sit in a branch of their own), and the gain of the whole row
+// is requested before the reduction instead of chunk by chunk behind it.
+template <int kCh>
+__global__ __launch_bounds__(kCtxThreads) void rmsnorm_forward_vec_kernel(RmsParams p) {
+  __shared__ float red[4];
+  const int64_t r = blockIdx.x;
+  const v4u zero4 = {0u, 0u, 0u, 0u};
+  v4u xraw[kCh][2], wraw[kCh][2];
+  LanePos q[kCh];
+  bool on[kCh];
+#pragma unroll
+  for (int ch = 0; ch < kCh; ++ch) {
+    q[ch] = row_pos(r, ch, p.ng);
+    on[ch] = q[ch].live && q[ch].c0 < p.cols;
+    const v4u* a = reinterpret_cast<const v4u*>(p.x + r * p.ld + (on[ch] ? q[ch].c0 : 0));
+    xraw[ch][0] = a[0];
+    xraw[ch][1] = a[1];
+  }
+#pragma unroll
+  for (int ch = 0; ch < kCh; ++ch) {
+    const v4u* a = reinterpret_cast<const v4u*>(p.w + (on[ch] ? q[ch].c0 : 0));
+    wraw[ch][0] = a[0];
+    wraw[ch][1] = a[1];
+  }
+  float xc[kValsPerLane];
+  float ss = 0.0f;
+#pragma unroll
+  for (int ch = 0; ch < kCh; ++ch) {
+    if (!on[ch]) xraw[ch][0] = xraw[ch][1] = zero4;
+    unpack16(xraw[ch], xc);
+#pragma unroll
+    for (int i = 0; i < kValsPerLane; ++i) ss = __builtin_fmaf(xc[i], xc[i], ss);
+  }
+  ss = block_sum(ss, red);
+  // keep only the packed row across the reduction: the floats are cheap to unpack again
+#pragma unroll
+  for (int ch = 0; ch < kCh; ++ch) asm volatile("" : "+v"(xraw[ch][0]), "+v"(xraw[ch][1]));
+  const float rstd = __fdiv_rn(1.0f, __fsqrt_rn(__fdiv_rn(ss, (float)p.cols) + p.eps));
+  if (threadIdx.x == 0) p.rstd[r] = rstd;
+#pragma unroll
+  for (int ch = 0; ch < kCh; ++ch) {
+    float w[kValsPerLane], y[kValsPerLane];
+    unpack16(xraw[ch], xc);
+    unpack16(wraw[ch], w);
+#pragma unroll
+    for (int i = 0; i < kValsPerLane; ++i) y[i] = xc[i] * rstd * w[i];
+    if (on[ch]) store16(p.y + r * p.ldy + q[ch].c0, true, q[ch].c0, p.cols, y);
+    quantize_store(xc, q[ch], p.packed, p.scales);
   }
 }
 
@@ -764,7 +887,13 @@ hipError_t launch_rmsnorm(const RmsParams& p, bool backward, hipStream_t st) {
   const int chunks = (p.ng + kRowChunkGroups - 1) / kRowChunkGroups;
   if (!backward) {
     if (p.rows == 0) return hipSuccess;
-    if (chunks <= kRmsMaxChunks)
+    const dim3 grid((unsigned)p.rows), block(kCtxThreads);
+    const bool vec = p.vec_ok && p.vec_w && p.cols % kValsPerLane == 0;
+    if (vec && chunks == 1) hipLaunchKernelGGL(rmsnorm_forward_vec_kernel<1>, grid, block, 0, st, p);
+    else if (vec && chunks == 2) hipLaunchKernelGGL(rmsnorm_forward_vec_kernel<2>, grid, block, 0, st, p);
+    else if (vec && chunks == 3) hipLaunchKernelGGL(rmsnorm_forward_vec_kernel<3>, grid, block, 0, st, p);
+    else if (vec && chunks == 4) hipLaunchKernelGGL(rmsnorm_forward_vec_kernel<4>, grid, block, 0, st, p);
+    else if (chunks <= kRmsMaxChunks)
       hipLaunchKernelGGL(rmsnorm_forward_kernel<true>, dim3((unsigned)p.rows), dim3(kCtxThreads), 0, st, p);
     else
       hipLaunchKernelGGL(rmsnorm_forward_kernel<false>, dim3((unsigned)p.rows), dim3(kCtxThreads), 0, st, p);
@@ -804,10 +933,14 @@ hipError_t launch_glu(const GluParams& p, bool backward, hipStream_t st) {
   if (p.n_groups == 0) return hipSuccess;
   const int64_t threads = p.n_groups * kLanesPerGroup;
   const unsigned grid = (unsigned)((threads + kCtxThreads - 1) / kCtxThreads);
-  if (backward)
-    hipLaunchKernelGGL(glu_backward_kernel, dim3(grid), dim3(kCtxThreads), 0, st, p);
-  else
-    hipLaunchKernelGGL(glu_forward_kernel, dim3(grid), dim3(kCtxThreads), 0, st, p);
+  const bool vec = p.vec_ok && p.cols % kValsPerLane == 0;
+  if (backward) {
+    if (vec) hipLaunchKernelGGL(glu_backward_vec_kernel, dim3(grid), dim3(kCtxThreads), 0, st, p);
+    else hipLaunchKernelGGL(glu_backward_kernel, dim3(grid), dim3(kCtxThreads), 0, st, p);
+  } else {
+    if (vec) hipLaunchKernelGGL(glu_forward_vec_kernel, dim3(grid), dim3(kCtxThreads), 0, st, p);
+    else hipLaunchKernelGGL(glu_forward_kernel, dim3(grid), dim3(kCtxThreads), 0, st, p);
+  }
   return hipGetLastError();
 }
 
