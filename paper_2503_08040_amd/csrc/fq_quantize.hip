@@ -279,6 +279,8 @@ void quantize_kernel(QuantParams p) {
       if (u) slot_early = atomicAdd(p.fb_count, 1);
       if (want_list) group_before = atomicOr(p.fb_words + (blk >> 5), my_bits(blk, u));
     }
+    // a flagged block has twice the work of the others and ends the kernel: it goes first
+    if (u) __builtin_amdgcn_s_setprio(3);
   }
 
   v4i q[4];
