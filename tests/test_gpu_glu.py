@@ -52,7 +52,9 @@ def _case(rows, cols, seed, scale1=3.0):
     return tuple(synth.to_bf16_bits(v) for v in (x1, x2, dy))
 
 
-@pytest.mark.parametrize("shape", [(64, 512), (33, 300), (1, 1), (5, 127), (7, 1001), (300, 8)])
+@pytest.mark.parametrize("shape", [(64, 512), (33, 300), (1, 1), (5, 127), (7, 1001), (300, 8),
+                                   # 16-byte rows (the vector kernels) whose last group is ragged or alone
+                                   (9, 144), (3, 16), (21, 4112), (5, 11008)])
 def test_glu_forward_backward(shape):
     b1, b2, bdy = _case(*shape, seed=shape[0] + shape[1])
     gu.announce(f"glu forward shape={shape}")
